@@ -1,0 +1,200 @@
+"""CPU oracle for the SharePrefill prefill hot path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to ``sp_oracle.c`` (plain C, fp64 arithmetic on fp32 inputs)
+plus the per-layer composition of its stages.  Only the tests, the smoke check
+and the benchmark's ``cpu_baseline`` leg may import this package; it shares no
+code with the HIP path and never imports it.
+
+Stages (one attention head at a time, arrays are float32 ``[N][d]``):
+
+* ``dense_rows``      causal softmax attention + block-mass score rows
+                      (Sec. 5.1 A(Q,K,V); Alg. 1 line 8 score map, mass reading)
+* ``build_mask_rows`` Alg. 2 per query-block row in exact fixed point, plus the
+                      forced sink and diagonal blocks
+* ``masked_rows``     Sec. 5.1 A(Q,K,V,M) over the listed key blocks
+* ``prefill_layer``   Alg. 1 / Alg. 4 for one layer with given pivots: pivots run
+                      dense, their score map becomes the cluster's pattern, all
+                      other heads of the cluster run masked attention with it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sp_oracle.c")
+_LIB = os.path.join(_HERE, "libsp_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile sp_oracle.c with gcc (OpenMP).  Returns the library path."""
+    if force or (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        fp = ctypes.POINTER(ctypes.c_float)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        L.spo_num_threads.restype = ctypes.c_int
+        L.spo_dense_rows.restype = ctypes.c_int
+        L.spo_dense_rows.argtypes = [fp, fp, fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                     ip, ctypes.c_int, fp, fp, fp]
+        L.spo_build_mask_rows.restype = ctypes.c_int
+        L.spo_build_mask_rows.argtypes = [fp, ip, ctypes.c_int, ctypes.c_int, ctypes.c_float, ip, ip, ip]
+        L.spo_masked_rows.restype = ctypes.c_int
+        L.spo_masked_rows.argtypes = [fp, fp, fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                      ip, ctypes.c_int, ip, ip, fp]
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().spo_num_threads())
+
+
+def _f(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _i(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _rows(rows, nqb):
+    if rows is None:
+        rows = np.arange(nqb, dtype=np.int32)
+    return np.ascontiguousarray(rows, dtype=np.int32)
+
+
+def dense_rows(q, k, v, block: int, rows: Optional[Sequence[int]] = None, scale: Optional[float] = None,
+               want_scores: bool = True):
+    """Dense causal attention of one head on the listed query-block rows.
+
+    Returns (o [nrows*B][d], scores [nrows][nkb] or None, lse [nrows*B])."""
+    q, qp = _f(q)
+    k, kp = _f(k)
+    v, vp = _f(v)
+    N, d = q.shape
+    assert k.shape == (N, d) and v.shape == (N, d)
+    nkb = N // block
+    rows = _rows(rows, nkb)
+    nr = len(rows)
+    scale = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    o = np.empty((nr * block, d), dtype=np.float32)
+    sc = np.empty((nr, nkb), dtype=np.float32) if want_scores else None
+    lse = np.empty((nr * block,), dtype=np.float32)
+    rc = _load().spo_dense_rows(qp, kp, vp, N, d, block, scale,
+                                rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), nr,
+                                o.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                                sc.ctypes.data_as(ctypes.POINTER(ctypes.c_float)) if want_scores else None,
+                                lse.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if rc:
+        raise ValueError(f"spo_dense_rows failed ({rc})")
+    return o, sc, lse
+
+
+def build_mask_rows(scores, gamma: float, row_ids: Optional[Sequence[int]] = None):
+    """Alg. 2 per row.  scores [nrows][nkb]; row r describes query block row_ids[r].
+
+    Returns (kb_idx int32 [nrows][nkb] ascending, -1 tail; kb_cnt int32 [nrows];
+    k_star int32 [nrows] = size of the thresholded set before forced blocks)."""
+    scores, sp = _f(scores)
+    nr, nkb = scores.shape
+    if row_ids is None:
+        assert nr == nkb
+    row_ids = _rows(row_ids, nkb)
+    assert len(row_ids) == nr
+    idx = np.empty((nr, nkb), dtype=np.int32)
+    cnt = np.empty((nr,), dtype=np.int32)
+    ks = np.empty((nr,), dtype=np.int32)
+    ip = ctypes.POINTER(ctypes.c_int32)
+    rc = _load().spo_build_mask_rows(sp, row_ids.ctypes.data_as(ip), nr, nkb, ctypes.c_float(np.float32(gamma)),
+                                     idx.ctypes.data_as(ip), cnt.ctypes.data_as(ip), ks.ctypes.data_as(ip))
+    if rc:
+        raise ValueError(f"spo_build_mask_rows failed ({rc})")
+    return idx, cnt, ks
+
+
+def masked_rows(q, k, v, block: int, kb_idx, kb_cnt, rows: Optional[Sequence[int]] = None,
+                scale: Optional[float] = None):
+    """Block-sparse causal attention of one head; kb_idx/kb_cnt are per listed row."""
+    q, qp = _f(q)
+    k, kp = _f(k)
+    v, vp = _f(v)
+    N, d = q.shape
+    nkb = N // block
+    rows = _rows(rows, nkb)
+    nr = len(rows)
+    kb_idx, xp = _i(kb_idx)
+    kb_cnt, cp = _i(kb_cnt)
+    assert kb_idx.shape == (nr, nkb) and kb_cnt.shape == (nr,)
+    scale = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    o = np.empty((nr * block, d), dtype=np.float32)
+    rc = _load().spo_masked_rows(qp, kp, vp, N, d, block, scale,
+                                 rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), nr, xp, cp,
+                                 o.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if rc:
+        raise ValueError(f"spo_masked_rows failed ({rc})")
+    return o
+
+
+def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: float,
+                  rows: Optional[Sequence[int]] = None, scale: Optional[float] = None,
+                  masks=None):
+    """One layer of pattern sharing with given pivots (Alg. 1 / Alg. 2 / Alg. 4).
+
+    q [N][Hq][d], k/v [N][Hkv][d] float32.  Returns a dict with
+      o       [nrows*B][Hq][d] float32
+      scores  [C][nrows][nkb]  float32 (pivot block-mass rows)
+      kb_idx  [C][nrows][nkb], kb_cnt [C][nrows]
+    Heads with cluster id -1 run dense.  `masks`, if given as (kb_idx, kb_cnt) with
+    those shapes, replaces the oracle's own pattern for the non-pivot heads (used
+    to check outputs against a pattern produced elsewhere)."""
+    q = np.asarray(q, dtype=np.float32)
+    k = np.asarray(k, dtype=np.float32)
+    v = np.asarray(v, dtype=np.float32)
+    N, Hq, d = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    nkb = N // block
+    rows = _rows(rows, nkb)
+    nr = len(rows)
+    C = len(pivot_heads)
+    o = np.zeros((nr * block, Hq, d), dtype=np.float32)
+    scores = np.zeros((C, nr, nkb), dtype=np.float32)
+    kb_idx = np.full((C, nr, nkb), -1, dtype=np.int32)
+    kb_cnt = np.zeros((C, nr), dtype=np.int32)
+    for c, p in enumerate(pivot_heads):
+        p = int(p)
+        assert int(head_to_cluster[p]) == c
+        g = p // G
+        op, sc, _ = dense_rows(q[:, p], k[:, g], v[:, g], block, rows, scale)
+        o[:, p] = op
+        scores[c] = sc
+        kb_idx[c], kb_cnt[c], _ = build_mask_rows(sc, gamma, rows)
+    if masks is not None:
+        kb_idx, kb_cnt = masks
+    pivots = {int(p) for p in pivot_heads}
+    for h in range(Hq):
+        if h in pivots:
+            continue
+        c = int(head_to_cluster[h])
+        g = h // G
+        if c < 0:
+            o[:, h], _, _ = dense_rows(q[:, h], k[:, g], v[:, g], block, rows, scale, want_scores=False)
+        else:
+            o[:, h] = masked_rows(q[:, h], k[:, g], v[:, g], block, kb_idx[c], kb_cnt[c], rows, scale)
+    return {"o": o, "scores": scores, "kb_idx": kb_idx, "kb_cnt": kb_cnt}

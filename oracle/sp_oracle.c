@@ -1,0 +1,279 @@
+/*
+ * CPU oracle for the SharePrefill prefill hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, obviously-correct C: fp32 inputs (bf16 values widened exactly),
+ * fp64 arithmetic inside, fp32 / int32 results.  Nothing here is blocked, fused
+ * or reordered beyond what the definitions state; the only parallelism is an
+ * OpenMP loop over independent query rows.  This file shares no code, header,
+ * table or helper with the HIP path and is never loaded by the product path.
+ *
+ * What is computed (per attention head; Q, K, V are [N][d] row-major float):
+ *
+ *   logits      x[t][s] = scale * sum_e Q[t][e] K[s][e],  only s <= t exists
+ *               (Sec. 5.1, the argument of the softmax in A(Q,K,V); causal
+ *               because this is decoder prefill).
+ *   dense       P[t][s] = exp(x[t][s] - max_s x[t][.]) / sum_s exp(.),
+ *               O[t] = sum_s P[t][s] V[s]              (Sec. 5.1, A(Q,K,V)).
+ *   scores      S[i][j] = (1/B) sum_{t in block i} sum_{s in block j, s<=t} P[t][s]
+ *               for j <= i, else 0: the exact attention mass of each
+ *               (query-block, key-block) pair, every row of S sums to 1.
+ *               (Alg. 1 line 8 returns a block-level score map next to O; the
+ *               per-block *mass* reading is the one this build is specified on.)
+ *   mask rows   Alg. 2 (argsort, minimal prefix whose cumulative score reaches
+ *               gamma) applied per query-block row in exact fixed point, then
+ *               the sink block 0 and the diagonal block i are added.
+ *   masked      Sec. 5.1, A(Q,K,V,M): softmax restricted to the key blocks with
+ *               M = 1 (excluded entries get weight exactly 0), renormalised.
+ *
+ * All functions take a list of query-block rows so that long sequences can be
+ * checked on a sample of rows: row i only needs Q block i and K/V[0 .. (i+1)B).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int spo_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* scaled logits of query t against keys [0, t] into x[0..t]; returns the max */
+static double logits_row(const float *q, const float *k, int t, int d, double scale, double *x) {
+  double mx = -INFINITY;
+  const float *qt = q + (size_t)t * d;
+  for (int s = 0; s <= t; ++s) {
+    const float *ks = k + (size_t)s * d;
+    double acc = 0.0;
+#pragma omp simd reduction(+ : acc)
+    for (int e = 0; e < d; ++e) acc += (double)qt[e] * (double)ks[e];
+    x[s] = acc * scale;
+    if (x[s] > mx) mx = x[s];
+  }
+  return mx;
+}
+
+/*
+ * Dense causal attention for the query blocks listed in rows[0..nrows).
+ *   o      [nrows][B][d]   attention output of those query blocks (may be NULL)
+ *   scores [nrows][nkb]    block-mass map rows (may be NULL), nkb = N / B
+ *   lse    [nrows][B]      natural-log sum-exp of each query row (may be NULL)
+ */
+int spo_dense_rows(const float *q, const float *k, const float *v, int N, int d, int B, double scale,
+                   const int *rows, int nrows, float *o, float *scores, float *lse) {
+  if (N <= 0 || d <= 0 || B <= 0 || N % B) return 1;
+  const int nkb = N / B;
+  for (int r = 0; r < nrows; ++r)
+    if (rows[r] < 0 || rows[r] >= nkb) return 1;
+  int fail = 0;
+#pragma omp parallel
+  {
+    double *x = (double *)malloc(sizeof(double) * (size_t)N);
+    double *acc = (double *)malloc(sizeof(double) * (size_t)d);
+    double *mass = (double *)malloc(sizeof(double) * (size_t)nkb);
+    if (!x || !acc || !mass) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int r = 0; r < nrows; ++r) {
+        const int i = rows[r];
+        for (int j = 0; j < nkb; ++j) mass[j] = 0.0;
+        for (int tt = 0; tt < B; ++tt) {
+          const int t = i * B + tt;
+          const double mx = logits_row(q, k, t, d, scale, x);
+          double den = 0.0;
+          for (int s = 0; s <= t; ++s) {
+            x[s] = exp(x[s] - mx);
+            den += x[s];
+          }
+          for (int e = 0; e < d; ++e) acc[e] = 0.0;
+          for (int s = 0; s <= t; ++s) {
+            const double p = x[s] / den;
+            mass[s / B] += p;
+            const float *vs = v + (size_t)s * d;
+            for (int e = 0; e < d; ++e) acc[e] += p * (double)vs[e];
+          }
+          if (o)
+            for (int e = 0; e < d; ++e) o[((size_t)r * B + tt) * d + e] = (float)acc[e];
+          if (lse) lse[(size_t)r * B + tt] = (float)(mx + log(den));
+        }
+        if (scores)
+          for (int j = 0; j < nkb; ++j) scores[(size_t)r * nkb + j] = (j <= i) ? (float)(mass[j] / B) : 0.0f;
+      }
+    }
+    free(x);
+    free(acc);
+    free(mass);
+  }
+  return fail ? 2 : 0;
+}
+
+/* ---- Alg. 2, per query-block row, in exact fixed point ------------------- */
+
+typedef struct {
+  uint32_t u;
+  int32_t j;
+} spo_key;
+
+static int key_cmp(const void *a, const void *b) {
+  const spo_key *x = (const spo_key *)a, *y = (const spo_key *)b;
+  if (x->u != y->u) return (x->u > y->u) ? -1 : 1; /* score descending */
+  return (x->j < y->j) ? -1 : (x->j > y->j);       /* ties: lower key block first */
+}
+
+static int int_cmp(const void *a, const void *b) {
+  const int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+  return (x < y) ? -1 : (x > y);
+}
+
+/* quantise a block score to 24 fractional bits: rint(clamp(s,0,1) * 2^24), NaN -> 0 */
+static uint32_t quantise(float s) {
+  if (!(s > 0.0f)) return 0u; /* also catches NaN */
+  if (s > 1.0f) s = 1.0f;
+  return (uint32_t)rintf(s * 16777216.0f);
+}
+
+/*
+ * scores  [nrows][nkb] block-score rows; row r describes query block row_ids[r]
+ * kb_idx  [nrows][nkb] selected key blocks, ascending, tail filled with -1
+ * kb_cnt  [nrows]
+ * k_star  [nrows] (may be NULL): size of the thresholded set before the forced
+ *         sink / diagonal blocks are added (for tests of minimality).
+ */
+int spo_build_mask_rows(const float *scores, const int *row_ids, int nrows, int nkb, float gamma,
+                        int32_t *kb_idx, int32_t *kb_cnt, int32_t *k_star) {
+  if (nkb <= 0 || nkb > 32768 || !(gamma > 0.0f) || gamma > 1.0f) return 1;
+  const uint64_t gq = (uint64_t)rintf(gamma * 16777216.0f);
+  spo_key *keys = (spo_key *)malloc(sizeof(spo_key) * (size_t)nkb);
+  int32_t *sel = (int32_t *)malloc(sizeof(int32_t) * ((size_t)nkb + 2));
+  if (!keys || !sel) {
+    free(keys);
+    free(sel);
+    return 2;
+  }
+  for (int r = 0; r < nrows; ++r) {
+    const int i = row_ids[r];
+    if (i < 0 || i >= nkb) {
+      free(keys);
+      free(sel);
+      return 1;
+    }
+    const float *row = scores + (size_t)r * nkb;
+    uint64_t tot = 0;
+    for (int j = 0; j <= i; ++j) {
+      keys[j].u = quantise(row[j]);
+      keys[j].j = j;
+      tot += keys[j].u;
+    }
+    qsort(keys, (size_t)i + 1, sizeof(spo_key), key_cmp);
+    int kstar = 0;
+    if (tot > 0) {
+      uint64_t cum = 0;
+      for (int kk = 0; kk <= i; ++kk) {
+        cum += keys[kk].u;
+        if ((cum << 24) >= gq * tot) { /* cum/tot >= gamma, exactly */
+          kstar = kk + 1;
+          break;
+        }
+      }
+    }
+    int n = 0, has0 = 0, hasi = 0;
+    for (int kk = 0; kk < kstar; ++kk) {
+      sel[n++] = keys[kk].j;
+      if (keys[kk].j == 0) has0 = 1;
+      if (keys[kk].j == i) hasi = 1;
+    }
+    if (!has0) {
+      sel[n++] = 0;
+      if (i == 0) hasi = 1;
+    }
+    if (!hasi) sel[n++] = i;
+    qsort(sel, (size_t)n, sizeof(int32_t), int_cmp);
+    int32_t *out = kb_idx + (size_t)r * nkb;
+    for (int j = 0; j < nkb; ++j) out[j] = (j < n) ? sel[j] : -1;
+    kb_cnt[r] = n;
+    if (k_star) k_star[r] = kstar;
+  }
+  free(keys);
+  free(sel);
+  return 0;
+}
+
+/*
+ * Masked (block-sparse) causal attention for the query blocks in rows[].
+ *   kb_idx [nrows][nkb], kb_cnt [nrows]: key blocks with M = 1 for each listed row
+ *   o      [nrows][B][d]
+ * A listed key block beyond the diagonal contributes nothing (causal).  A query
+ * with no admissible key yields a zero output row.
+ */
+int spo_masked_rows(const float *q, const float *k, const float *v, int N, int d, int B, double scale,
+                    const int *rows, int nrows, const int32_t *kb_idx, const int32_t *kb_cnt, float *o) {
+  if (N <= 0 || d <= 0 || B <= 0 || N % B) return 1;
+  const int nkb = N / B;
+  for (int r = 0; r < nrows; ++r) {
+    if (rows[r] < 0 || rows[r] >= nkb || kb_cnt[r] < 0 || kb_cnt[r] > nkb) return 1;
+    for (int c = 0; c < kb_cnt[r]; ++c) {
+      const int j = kb_idx[(size_t)r * nkb + c];
+      if (j < 0 || j >= nkb) return 1;
+    }
+  }
+  int fail = 0;
+#pragma omp parallel
+  {
+    double *x = (double *)malloc(sizeof(double) * (size_t)N);
+    double *acc = (double *)malloc(sizeof(double) * (size_t)d);
+    unsigned char *on = (unsigned char *)malloc((size_t)nkb);
+    if (!x || !acc || !on) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int r = 0; r < nrows; ++r) {
+        const int i = rows[r];
+        memset(on, 0, (size_t)nkb);
+        for (int c = 0; c < kb_cnt[r]; ++c) on[kb_idx[(size_t)r * nkb + c]] = 1;
+        for (int tt = 0; tt < B; ++tt) {
+          const int t = i * B + tt;
+          const float *qt = q + (size_t)t * d;
+          double mx = -INFINITY;
+          for (int s = 0; s <= t; ++s) {
+            if (!on[s / B]) continue;
+            const float *ks = k + (size_t)s * d;
+            double a = 0.0;
+#pragma omp simd reduction(+ : a)
+            for (int e = 0; e < d; ++e) a += (double)qt[e] * (double)ks[e];
+            x[s] = a * scale;
+            if (x[s] > mx) mx = x[s];
+          }
+          double den = 0.0;
+          for (int s = 0; s <= t; ++s) {
+            if (!on[s / B]) continue;
+            x[s] = exp(x[s] - mx);
+            den += x[s];
+          }
+          for (int e = 0; e < d; ++e) acc[e] = 0.0;
+          if (den > 0.0) {
+            for (int s = 0; s <= t; ++s) {
+              if (!on[s / B]) continue;
+              const double p = x[s] / den;
+              const float *vs = v + (size_t)s * d;
+              for (int e = 0; e < d; ++e) acc[e] += p * (double)vs[e];
+            }
+          }
+          for (int e = 0; e < d; ++e) o[((size_t)r * B + tt) * d + e] = (float)acc[e];
+        }
+      }
+    }
+    free(x);
+    free(acc);
+    free(on);
+  }
+  return fail ? 2 : 0;
+}
