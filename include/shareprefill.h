@@ -1,0 +1,133 @@
+/*
+ * libshareprefill -- SharePrefill long-context prefill attention for one layer,
+ * hand-written for AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * The method (Sec. 5.2): inside every cluster of similar attention heads one
+ * pivotal head runs dense causal attention; its exact attention is reduced to a
+ * per-(query-block, key-block) score map; the map becomes a block mask (per
+ * query-block row, the smallest set of key blocks whose cumulative score reaches
+ * gamma -- Alg. 2 -- plus the sink block and the diagonal block); every other
+ * head of the cluster then runs block-sparse attention A(Q,K,V,M) (Sec. 5.1)
+ * over only those blocks (Alg. 4: pattern sharing).
+ *
+ * Conventions for every call
+ *   - "device" pointers are HIP device memory owned by the caller; "host"
+ *     pointers are ordinary host memory read synchronously during the call.
+ *   - The library never allocates or frees device memory; scratch space comes in
+ *     through `workspace` (size from sp_workspace_bytes, 256-byte aligned).
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without waiting for it.
+ *   - Arguments are validated first; on any error nothing is launched, the
+ *     status says why and sp_last_error() (thread-local) has the detail.
+ *   - Results are deterministic: no floating-point atomics anywhere.
+ *   - Q, K, V, O are bfloat16.  Element strides (not bytes) are given per batch,
+ *     token and head; head_dim is contiguous; every row start must be 16-byte
+ *     aligned (strides multiples of 8 elements).
+ *   - Supported envelope: head_dim in {64,128}, block in {64,128},
+ *     seq % 128 == 0, seq / block <= 32768, n_q_heads % n_kv_heads == 0.
+ *     Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ */
+#ifndef SHAREPREFILL_H
+#define SHAREPREFILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SP_OK = 0,
+  SP_ERR_INVALID_ARG = 1, /* null pointer, bad size / stride / id, gamma out of (0,1] */
+  SP_ERR_UNSUPPORTED = 2, /* outside the supported envelope above */
+  SP_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or too small */
+  SP_ERR_HIP = 4          /* a HIP call or kernel launch failed */
+} sp_status;
+
+/* Geometry of one attention layer.  Strides are in elements. */
+typedef struct {
+  int32_t batch, seq, n_q_heads, n_kv_heads, head_dim, block;
+  int64_t q_stride_b, q_stride_t, q_stride_h;
+  int64_t kv_stride_b, kv_stride_t, kv_stride_h; /* shared by K and V */
+  int64_t o_stride_b, o_stride_t, o_stride_h;
+  float softmax_scale; /* 0 => 1/sqrt(head_dim) */
+} sp_shape;
+
+const char *sp_status_string(sp_status s);
+const char *sp_last_error(void);
+
+/*
+ * Bytes of device workspace needed by the calls below for this shape when at most
+ * `n_dense_heads` heads per batch entry run dense attention *with* block scores in
+ * one call (0 if no scores are ever requested).
+ */
+sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_t *bytes);
+
+/*
+ * Dense causal attention A(Q,K,V) (Sec. 5.1) for the listed query heads, and the
+ * block score map that Alg. 1 line 8 returns next to O, in the block-mass form:
+ *   S[i][j] = (1/block) * sum_{t in query block i} sum_{s in key block j, s<=t} P[t][s]
+ * (0 for j > i; every row sums to 1), P being the causal softmax of QK^T*scale.
+ *   q,k,v        device bf16
+ *   head_ids     host  [n_heads]  distinct query-head ids
+ *   o            device bf16; only the listed heads' rows are written
+ *   block_scores device fp32 [batch][n_heads][nqb][nkb] or NULL (no scores)
+ */
+sp_status sp_dense_attn_with_block_scores(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                          const int32_t *head_ids, int32_t n_heads, void *o,
+                                          float *block_scores, void *workspace, size_t workspace_bytes,
+                                          void *hip_stream);
+
+/*
+ * Alg. 2 (Construct Pivotal Pattern) applied to every query-block row of every map,
+ * in exact integer arithmetic: u_j = rint(clamp(S[i][j],0,1) * 2^24) (NaN -> 0) for
+ * j <= i; order by (u descending, j ascending); k* = the least k >= 1 whose prefix sum
+ * times 2^24 reaches rint(gamma * 2^24) * sum_j u_j (k* = 0 when every u_j is 0);
+ * the row's key-block set is that prefix plus block 0 (sink) and block i (diagonal).
+ *   block_scores device fp32 [n_maps][nqb][nkb]   (nqb == nkb required)
+ *   kb_idx       device int32 [n_maps][nqb][nkb]  ascending key blocks, tail = -1
+ *   kb_cnt       device int32 [n_maps][nqb]
+ *   bitmask      device uint64 [n_maps][nqb][ceil(nkb/64)] or NULL (bit j of word j/64)
+ */
+sp_status sp_build_block_mask(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb, float gamma,
+                              int32_t *kb_idx, int32_t *kb_cnt, uint64_t *bitmask, void *hip_stream);
+
+/*
+ * Block-sparse causal attention A(Q,K,V,M) (Sec. 5.1) for the listed heads: query
+ * block i of listed head n attends only to the key blocks
+ * kb_idx[b][head_map[n]][i][0 .. kb_cnt[b][head_map[n]][i]) (ascending, each <= i;
+ * blocks with M = 0 get weight exactly 0 and the softmax is renormalised).
+ *   head_ids host [n_heads] distinct query heads; head_map host [n_heads] in [0,n_maps)
+ *   kb_idx   device int32 [batch][n_maps][nqb][nkb]; kb_cnt device int32 [batch][n_maps][nqb]
+ *   o        device bf16; only the listed heads' rows are written
+ * Entries of a list that are out of range or above the diagonal are skipped; a
+ * query block whose list is empty gets zeros.  The packed K/V copy lives in
+ * `workspace`.
+ */
+sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void *k, const void *v,
+                               const int32_t *head_ids, const int32_t *head_map, int32_t n_heads,
+                               const int32_t *kb_idx, const int32_t *kb_cnt, int32_t n_maps, void *o,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One layer of pattern sharing (Alg. 1 with the pattern source of Alg. 4 and the
+ * pattern construction of Alg. 2): pivot heads run dense attention with block
+ * scores, each cluster's score map becomes its key-block lists, and every other
+ * clustered head runs block-sparse attention over its cluster's lists.
+ *   head_to_cluster host [n_q_heads]  cluster id in [0,n_clusters) or -1 (runs dense)
+ *   pivot_heads     host [n_clusters] pivot_heads[c] must lie in cluster c
+ *   o               device bf16, every head written
+ *   block_scores    device fp32 [batch][n_clusters][nqb][nkb]   (required, output)
+ *   kb_idx, kb_cnt  device int32 [batch][n_clusters][nqb][nkb] / [..][nqb] (required, output)
+ *   workspace       sized by sp_workspace_bytes(shape, n_clusters, ..)
+ */
+sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
+                           const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                           float gamma, void *o, float *block_scores, int32_t *kb_idx, int32_t *kb_cnt,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHAREPREFILL_H */

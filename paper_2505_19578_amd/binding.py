@@ -1,0 +1,138 @@
+"""ctypes binding of libshareprefill.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name (include/shareprefill.h).
+Device buffers are torch tensors (used as typed device pointers); small id arrays
+are host int32 sequences.  Calls enqueue on torch's current HIP stream.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Sequence
+
+from .build import library_path
+
+EXPORTED_SYMBOLS = [
+    "sp_status_string", "sp_last_error", "sp_workspace_bytes",
+    "sp_dense_attn_with_block_scores", "sp_build_block_mask",
+    "sp_block_sparse_attn", "sp_prefill_layer",
+]
+
+
+class SpShape(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("seq", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("block", ctypes.c_int32),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_t", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("kv_stride_b", ctypes.c_int64), ("kv_stride_t", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64),
+        ("o_stride_b", ctypes.c_int64), ("o_stride_t", ctypes.c_int64), ("o_stride_h", ctypes.c_int64),
+        ("softmax_scale", ctypes.c_float),
+    ]
+
+
+class SpError(RuntimeError):
+    def __init__(self, status: int, name: str, detail: str):
+        super().__init__(f"{name}: {detail}")
+        self.status = status
+        self.status_name = name
+        self.detail = detail
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libshareprefill.so (built on demand if absent); raises if that fails."""
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(library_path())
+        vp, ip, fp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p
+        sp = ctypes.POINTER(SpShape)
+        L.sp_status_string.restype = ctypes.c_char_p
+        L.sp_status_string.argtypes = [ctypes.c_int]
+        L.sp_last_error.restype = ctypes.c_char_p
+        L.sp_last_error.argtypes = []
+        L.sp_workspace_bytes.restype = ctypes.c_int
+        L.sp_workspace_bytes.argtypes = [sp, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
+        L.sp_dense_attn_with_block_scores.restype = ctypes.c_int
+        L.sp_dense_attn_with_block_scores.argtypes = [sp, vp, vp, vp, ip, ctypes.c_int32, vp, fp, vp,
+                                                      ctypes.c_size_t, vp]
+        L.sp_build_block_mask.restype = ctypes.c_int
+        L.sp_build_block_mask.argtypes = [fp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                          vp, vp, vp, vp]
+        L.sp_block_sparse_attn.restype = ctypes.c_int
+        L.sp_block_sparse_attn.argtypes = [sp, vp, vp, vp, ip, ip, ctypes.c_int32, vp, vp, ctypes.c_int32, vp,
+                                           vp, ctypes.c_size_t, vp]
+        L.sp_prefill_layer.restype = ctypes.c_int
+        L.sp_prefill_layer.argtypes = [sp, vp, vp, vp, ip, ip, ctypes.c_int32, ctypes.c_float, vp, fp, vp, vp,
+                                       vp, ctypes.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        L = lib()
+        raise SpError(rc, L.sp_status_string(rc).decode(), L.sp_last_error().decode())
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _ids(seq: Sequence[int]):
+    arr = (ctypes.c_int32 * len(seq))(*[int(x) for x in seq])
+    return arr
+
+
+def _stream() -> ctypes.c_void_p:
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def shape_of(q, k, o=None, block: int = 128, softmax_scale: float = 0.0) -> SpShape:
+    """sp_shape for token-major tensors q [b][t][hq][d], k/v [b][t][hkv][d] (any strides, d contiguous)."""
+    assert q.dim() == 4 and k.dim() == 4 and q.stride(3) == 1 and k.stride(3) == 1
+    o = q if o is None else o
+    s = SpShape()
+    s.batch, s.seq, s.n_q_heads, s.head_dim = q.shape
+    s.n_kv_heads = k.shape[2]
+    s.block = block
+    s.q_stride_b, s.q_stride_t, s.q_stride_h = q.stride(0), q.stride(1), q.stride(2)
+    s.kv_stride_b, s.kv_stride_t, s.kv_stride_h = k.stride(0), k.stride(1), k.stride(2)
+    s.o_stride_b, s.o_stride_t, s.o_stride_h = o.stride(0), o.stride(1), o.stride(2)
+    s.softmax_scale = softmax_scale
+    return s
+
+
+def sp_workspace_bytes(shape: SpShape, n_dense_heads: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().sp_workspace_bytes(ctypes.byref(shape), n_dense_heads, ctypes.byref(n)))
+    return int(n.value)
+
+
+def sp_dense_attn_with_block_scores(shape: SpShape, q, k, v, head_ids, o, block_scores, workspace):
+    _check(lib().sp_dense_attn_with_block_scores(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_ids), len(head_ids), _ptr(o),
+        _ptr(block_scores), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sp_build_block_mask(block_scores, n_maps: int, nqb: int, nkb: int, gamma: float, kb_idx, kb_cnt,
+                        bitmask=None):
+    _check(lib().sp_build_block_mask(_ptr(block_scores), n_maps, nqb, nkb, ctypes.c_float(gamma),
+                                     _ptr(kb_idx), _ptr(kb_cnt), _ptr(bitmask), _stream()))
+
+
+def sp_block_sparse_attn(shape: SpShape, q, k, v, head_ids, head_map, kb_idx, kb_cnt, n_maps: int, o, workspace):
+    assert len(head_ids) == len(head_map)
+    _check(lib().sp_block_sparse_attn(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_ids), _ids(head_map), len(head_ids),
+        _ptr(kb_idx), _ptr(kb_cnt), n_maps, _ptr(o), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sp_prefill_layer(shape: SpShape, q, k, v, head_to_cluster, pivot_heads, gamma: float, o, block_scores,
+                     kb_idx, kb_cnt, workspace):
+    _check(lib().sp_prefill_layer(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_to_cluster), _ids(pivot_heads),
+        len(pivot_heads), ctypes.c_float(gamma), _ptr(o), _ptr(block_scores), _ptr(kb_idx), _ptr(kb_cnt),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))

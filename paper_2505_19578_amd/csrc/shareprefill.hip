@@ -1,0 +1,848 @@
+// SharePrefill prefill attention for one layer on gfx950 (MI355X): HIP kernels + C ABI.
+//
+// Kernels
+//   pack_kv_kernel   K/V [token][kv head][d] -> per (kv head, 64-key sub-tile) images laid out
+//                    in MFMA-operand order, so the attention kernels move a sub-tile from HBM
+//                    to LDS as a straight copy (global_load_lds) and read every MFMA operand
+//                    with one conflict-free ds_read_b128.
+//   attn_kernel      flash-attention sweep (bf16 MFMA 32x32x16, fp32 online softmax in the
+//                    log2 domain).  DENSE=true walks key blocks 0..i and records, per query
+//                    and key block, the block-local log-sum-exp, from which the block-mass
+//                    score map is reduced in the epilogue (Sec. 5.1 A(Q,K,V); Alg. 1 line 8).
+//                    DENSE=false walks a per-row key-block index list (Sec. 5.1 A(Q,K,V,M)).
+//   mask_kernel      Alg. 2 per query-block row in exact integer arithmetic, one wavefront
+//                    per row: threshold search + ballot/popcount prefix sums.
+//
+// MFMA operand mapping (v_mfma_f32_32x32x16_bf16, 64 lanes, lane = 32*h + c):
+//   A (32 x 16): lane holds row c, k = 8h .. 8h+7        B (16 x 32): lane holds column c, same k
+//   D (32 x 32): lane holds column c, rows 8*(r/4) + 4h + (r%4) for accumulator r = 0..15
+// The kernel computes S^T = K Q^T (A = keys, B = queries) so that one lane owns one query:
+// the row-wise softmax needs only a single cross-lane exchange (lane ^ 32).  The accumulator
+// registers of S^T, rounded to bf16, are directly the B operand of O^T = V^T P^T provided the
+// V^T operand uses the matching key order inside each 16-key step (slot (h,e) <-> key
+// 4h+e for e<4, 8+4h+(e-4) for e>=4); pack_kv_kernel writes V in exactly that order.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+
+#include "shareprefill.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int SP_MAX_HEADS = 128;
+constexpr int KT = 64;  // keys per sub-tile
+
+thread_local char g_err[512] = "";
+
+void set_err(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+// ---------------------------------------------------------------------------------------------
+// pack kernel
+// ---------------------------------------------------------------------------------------------
+struct PackParams {
+  const uint16_t *k, *v;
+  char *out;
+  int64_t sb, st, sh;  // kv strides (elements)
+  int n_kv_heads, n_sub;  // n_sub = seq / 64
+};
+
+// One workgroup packs one (batch, kv head, 64-key sub-tile): K image then V image.
+template <int D>
+__global__ __launch_bounds__(256) void pack_kv_kernel(PackParams p) {
+  constexpr int IMG = KT * D * 2;       // bytes of one packed K (or V) image
+  constexpr int NCH = IMG / 16;         // 16-byte chunks per image
+  constexpr int DS = D / 16;
+  constexpr int VROW = D + 8;           // padded LDS row (elements)
+  __shared__ __attribute__((aligned(16))) uint16_t vs[KT * VROW];
+  const int kt = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int64_t base = (int64_t)b * p.sb + (int64_t)kt * KT * p.st + (int64_t)kvh * p.sh;
+  char *out = p.out + (((int64_t)b * p.n_kv_heads + kvh) * p.n_sub + kt) * (int64_t)(2 * IMG);
+
+  // stage V rows into LDS (row-major, padded)
+  for (int c = tid; c < KT * (D / 8); c += 256) {
+    const int key = c / (D / 8), part = c % (D / 8);
+    const u32x4 val = *reinterpret_cast<const u32x4 *>(p.v + base + (int64_t)key * p.st + part * 8);
+    *reinterpret_cast<u32x4 *>(&vs[key * VROW + part * 8]) = val;
+  }
+  // K image: fragment f = rb*DS + ds, lane holds key 32rb + c, d = 16ds + 8h ..+7
+  for (int c = tid; c < NCH; c += 256) {
+    const int f = c >> 6, lane = c & 63;
+    const int rb = f / DS, ds = f % DS;
+    const int key = 32 * rb + (lane & 31), dpos = 16 * ds + 8 * (lane >> 5);
+    const u32x4 val = *reinterpret_cast<const u32x4 *>(p.k + base + (int64_t)key * p.st + dpos);
+    *reinterpret_cast<u32x4 *>(out + (int64_t)c * 16) = val;
+  }
+  __syncthreads();
+  // V image: fragment f = db*4 + ks, lane holds dd = 32db + c, keys 16ks + slot(h, e)
+  for (int c = tid; c < NCH; c += 256) {
+    const int f = c >> 6, lane = c & 63;
+    const int db = f >> 2, ks = f & 3;
+    const int dd = 32 * db + (lane & 31), h = lane >> 5;
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const int e = 2 * e2;
+      const int key0 = 16 * ks + ((e < 4) ? (4 * h + e) : (8 + 4 * h + (e - 4)));
+      const uint32_t lo = vs[key0 * VROW + dd], hi = vs[(key0 + 1) * VROW + dd];
+      w[e2] = lo | (hi << 16);
+    }
+    u32x4 val = {w[0], w[1], w[2], w[3]};
+    *reinterpret_cast<u32x4 *>(out + IMG + (int64_t)c * 16) = val;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// attention kernel
+// ---------------------------------------------------------------------------------------------
+struct AttnParams {
+  const uint16_t *q;
+  const char *kvp;  // packed K/V images
+  uint16_t *o;
+  int64_t q_sb, q_st, q_sh, o_sb, o_st, o_sh;
+  int seq, nqb, n_kv_heads, group, n_heads, n_maps;
+  float c;  // softmax scale * log2(e)
+  float *lws;     // dense: block-local log2-sum-exp [b][n][nqb][nkb][B], or null
+  float *scores;  // dense: [b][n][nqb][nkb], or null
+  const int32_t *kb_idx;  // sparse: [b][n_maps][nqb][nkb]
+  const int32_t *kb_cnt;  // sparse: [b][n_maps][nqb]
+  int32_t head_ids[SP_MAX_HEADS];
+  int32_t head_map[SP_MAX_HEADS];
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+__device__ __forceinline__ float xor32(float x) {
+  return __shfl_xor(x, 32, 64);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 t = {a, b};
+  bf16x2 r = __builtin_convertvector(t, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+template <int D, int B, bool DENSE>
+__global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
+  constexpr int NW = B / 32;        // wavefronts per workgroup, 32 queries each
+  constexpr int SPB = B / KT;       // sub-tiles per key block
+  constexpr int IMG = KT * D * 2;   // bytes of a packed K (or V) image
+  constexpr int STAGE = 2 * IMG;    // K image + V image
+  constexpr int DS = D / 16;        // k-steps of the QK^T product
+  constexpr int DB = D / 32;        // 32-row blocks of O^T
+  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
+  __shared__ float lse_sh[B];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, c32 = lane & 31;
+  // workgroup -> (batch, listed head, query block): heads fastest, long rows first
+  int bid = blockIdx.x;
+  const int hslot = bid % p.n_heads;
+  bid /= p.n_heads;
+  const int i = p.nqb - 1 - (bid % p.nqb);
+  const int b = bid / p.nqb;
+  const int head = p.head_ids[hslot];
+  const int kvh = head / p.group;
+  const int nkb = p.nqb;
+
+  const int tq = 32 * w + c32;  // this lane's query inside the block
+  const uint16_t *qp = p.q + (int64_t)b * p.q_sb + ((int64_t)i * B + tq) * p.q_st + (int64_t)head * p.q_sh + 8 * h;
+  bf16x8 qf[DS];
+#pragma unroll
+  for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
+
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float m = -INFINITY, l = 0.f, bs = 0.f;
+
+  int nblk;
+  const int32_t *list = nullptr;
+  if (DENSE) {
+    nblk = i + 1;
+  } else {
+    const int64_t row = ((int64_t)b * p.n_maps + p.head_map[hslot]) * p.nqb + i;
+    nblk = p.kb_cnt[row];
+    nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
+    list = p.kb_idx + row * nkb;
+  }
+  const int nsub = nblk * SPB;
+  const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
+  float *lrow = nullptr;
+  if (DENSE && p.lws) lrow = p.lws + ((((int64_t)b * p.n_heads + hslot) * p.nqb + i) * nkb) * B + tq;
+
+  auto block_of = [&](int e, bool &valid) -> int {
+    if (DENSE) {
+      valid = true;
+      return e;
+    }
+    const int j = list[e];
+    valid = (j >= 0) && (j <= i);
+    return valid ? j : 0;
+  };
+  auto issue = [&](int it, int sel) {
+    bool valid;
+    const int j = block_of(it / SPB, valid);
+    const char *src = kvbase + (int64_t)(j * SPB + it % SPB) * STAGE + lane * 16;
+    char *dst = smem + sel * STAGE;
+#pragma unroll
+    for (int n = 0; n < STAGE / 1024 / NW; ++n) {
+      const int ch = w + n * NW;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + ch * 1024),
+                                       (__attribute__((address_space(3))) void *)(dst + ch * 1024), 16, 0, 0);
+    }
+  };
+
+  if (nsub > 0) issue(0, 0);
+  for (int it = 0; it < nsub; ++it) {
+    __builtin_amdgcn_s_waitcnt(0);  // own LDS-direct loads have landed
+    __syncthreads();                // everyone's have; previous tile's readers are done
+    if (it + 1 < nsub) issue(it + 1, (it + 1) & 1);
+
+    const int sub = it % SPB;
+    bool valid;
+    const int j = block_of(it / SPB, valid);
+    int mode = valid ? 0 : 2;  // 0 = no mask, 1 = causal mask inside the tile, 2 = nothing to do
+    if (valid && j == i) {
+      const int klo = KT * sub, qlo = 32 * w;
+      mode = (klo > qlo + 31) ? 2 : ((klo + KT - 1 <= qlo) ? 0 : 1);
+    }
+    if (mode != 2) {
+      const char *kb = smem + (it & 1) * STAGE + lane * 16;
+      const char *vb = kb + IMG;
+      f32x16 s[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kb + (rb * DS + ds) * 1024);
+          s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ds], s[rb], 0, 0, 0);
+        }
+      }
+      if (mode == 1) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kk = KT * sub + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+            if (kk > tq) s[rb][r] = -INFINITY;
+          }
+      }
+      float mx = s[0][0];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[rb][r]);
+      mx = fmaxf(mx, xor32(mx));
+      const float m_new = fmaxf(m, mx * p.c);
+      const float alpha = fast_exp2(m - m_new);
+      float rs = 0.f;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float pv = fast_exp2(__builtin_fmaf(s[rb][r], p.c, -m_new));
+          s[rb][r] = pv;
+          rs += pv;
+        }
+      rs += xor32(rs);
+      l = l * alpha + rs;
+      bs = bs * alpha + rs;
+      m = m_new;
+      if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+      }
+      bf16x8 pb[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        u32x4 t;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2)
+          t[e2] = pack_bf16(s[ks >> 1][8 * (ks & 1) + 2 * e2], s[ks >> 1][8 * (ks & 1) + 2 * e2 + 1]);
+        pb[ks] = __builtin_bit_cast(bf16x8, t);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vb + (db * 4 + ks) * 1024);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks], oacc[db], 0, 0, 0);
+        }
+      }
+    }
+    if (DENSE && sub == SPB - 1) {
+      // end of key block j: record log2 of the block's exp-sum for this lane's query
+      if (lrow && h == 0) lrow[(int64_t)j * B] = m + fast_log2(bs);
+      bs = 0.f;
+    }
+  }
+
+  // ---- output: O = O^T accumulators / l, rounded to bf16 ----
+  const float inv = (l > 0.f) ? 1.f / l : 0.f;
+  uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)i * B + tq) * p.o_st + (int64_t)head * p.o_sh;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      u32x2 t;
+      t[0] = pack_bf16(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv);
+      t[1] = pack_bf16(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
+      *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * g + 4 * h) = t;
+    }
+
+  // ---- block-mass scores: S[i][j] = (1/B) sum_t 2^(lws[j][t] - L_t) ----
+  if (DENSE && p.scores) {
+    if (h == 0) lse_sh[tq] = m + fast_log2(l);
+    __threadfence();
+    __syncthreads();
+    const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hslot) * p.nqb + i) * nkb) * B;
+    float *srow = p.scores + (((int64_t)b * p.n_heads + hslot) * p.nqb + i) * nkb;
+    for (int j = w; j <= i; j += NW) {
+      float acc = 0.f;
+#pragma unroll
+      for (int t = lane; t < B; t += 64) acc += fast_exp2(lblk[(int64_t)j * B + t] - lse_sh[t]);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+      if (lane == 0) srow[j] = acc * (1.f / B);
+    }
+    for (int j = i + 1 + tid; j < nkb; j += NW * 64) srow[j] = 0.f;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// mask kernel (Alg. 2 per row, exact integers)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+__device__ __forceinline__ uint32_t quantise24(float s) {
+  if (!(s > 0.f)) return 0u;  // negative, zero and NaN
+  if (s > 1.f) s = 1.f;
+  return (uint32_t)rintf(s * 16777216.f);
+}
+
+// One wavefront per (map, row).  EPL > 0: the row lives in registers (nkb <= 64*EPL);
+// EPL == 0: any nkb, the row is re-read from memory in every pass.
+template <int EPL>
+__global__ __launch_bounds__(256) void mask_kernel(const float *__restrict__ scores, int n_rows_total, int nqb,
+                                                   int nkb, uint32_t gq, int32_t *__restrict__ kb_idx,
+                                                   int32_t *__restrict__ kb_cnt, uint64_t *__restrict__ bitmask) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows_total) return;
+  const int i = row % nqb;
+  const float *src = scores + (int64_t)row * nkb;
+  const int nchunk = (i >> 6) + 1;  // 64-wide chunks that hold valid key blocks
+  uint32_t u[EPL > 0 ? EPL : 1];
+  auto get = [&](int e) -> uint32_t {
+    if (EPL > 0) return u[e];
+    const int j = e * 64 + lane;
+    return (j <= i) ? quantise24(src[j]) : 0u;
+  };
+  if (EPL > 0) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const int j = e * 64 + lane;
+      u[e] = (j <= i) ? quantise24(src[j]) : 0u;
+    }
+  }
+  auto sum_ge = [&](uint32_t v) -> uint64_t {
+    uint64_t part = 0;
+    if (EPL > 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) part += (u[e] >= v) ? u[e] : 0u;
+    } else {
+      for (int e = 0; e < nchunk; ++e) {
+        const uint32_t x = get(e);
+        part += (x >= v) ? x : 0u;
+      }
+    }
+    return wave_sum_u64(part);
+  };
+  const uint64_t tot = sum_ge(1u);
+  uint32_t vstar = 0xFFFFFFFFu;  // nothing reaches it: only forced blocks when tot == 0
+  uint64_t need = 0;
+  if (tot > 0) {
+    uint64_t T = ((uint64_t)gq * tot + 16777215ull) >> 24;  // least integer prefix sum that reaches gamma
+    if (T < 1) T = 1;
+    uint32_t lo = 1u, hi = 16777217u;  // sum_ge(lo) >= T > sum_ge(hi)
+    while (hi - lo > 1u) {
+      const uint32_t mid = lo + ((hi - lo) >> 1);
+      if (sum_ge(mid) >= T) lo = mid; else hi = mid;
+    }
+    vstar = lo;
+    const uint64_t above = sum_ge(vstar + 1u);
+    need = (T - above + vstar - 1) / vstar;  // ties taken, lowest key block first
+  }
+  int32_t *out = kb_idx + (int64_t)row * nkb;
+  const int nwords = (nkb + 63) >> 6;
+  const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  uint32_t ties_before = 0, n_out = 0;
+  const int nch_all = EPL > 0 ? EPL : nwords;
+  for (int e = 0; e < nch_all; ++e) {
+    if (e >= nwords) break;
+    const int j = e * 64 + lane;
+    uint32_t x = 0;
+    if (EPL > 0) {
+#pragma unroll
+      for (int ee = 0; ee < EPL; ++ee)
+        if (ee == e) x = u[ee];
+    } else {
+      x = (e < nchunk) ? get(e) : 0u;
+    }
+    const bool tie = (j <= i) && (x == vstar);
+    const uint64_t tmask = __ballot(tie);
+    const uint32_t trank = ties_before + __popcll(tmask & lt);
+    ties_before += __popcll(tmask);
+    const bool sel = (j <= i) && ((x > vstar && vstar != 0xFFFFFFFFu) || (tie && trank < need) || j == 0 || j == i);
+    const uint64_t smask = __ballot(sel);
+    if (sel) out[n_out + __popcll(smask & lt)] = j;
+    n_out += __popcll(smask);
+    if (bitmask && lane == 0) bitmask[(int64_t)row * nwords + e] = smask;
+  }
+  for (int pos = n_out + lane; pos < nkb; pos += 64) out[pos] = -1;
+  if (lane == 0) kb_cnt[row] = (int32_t)n_out;
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+sp_status check_shape(const sp_shape *s) {
+  if (!s) {
+    set_err("shape is NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (s->batch <= 0 || s->seq <= 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0) {
+    set_err("batch/seq/head counts must be positive");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (s->n_q_heads % s->n_kv_heads) {
+    set_err("n_q_heads (%d) is not a multiple of n_kv_heads (%d)", s->n_q_heads, s->n_kv_heads);
+    return SP_ERR_INVALID_ARG;
+  }
+  if (s->head_dim != 64 && s->head_dim != 128) {
+    set_err("head_dim %d unsupported (64 or 128)", s->head_dim);
+    return SP_ERR_UNSUPPORTED;
+  }
+  if (s->block != 64 && s->block != 128) {
+    set_err("block %d unsupported (64 or 128)", s->block);
+    return SP_ERR_UNSUPPORTED;
+  }
+  if (s->seq % 128) {
+    set_err("seq %d is not a multiple of 128", s->seq);
+    return SP_ERR_UNSUPPORTED;
+  }
+  if (s->seq / s->block > 32768) {
+    set_err("seq/block = %d exceeds 32768", s->seq / s->block);
+    return SP_ERR_UNSUPPORTED;
+  }
+  if (s->n_q_heads > SP_MAX_HEADS) {
+    set_err("n_q_heads %d exceeds %d", s->n_q_heads, SP_MAX_HEADS);
+    return SP_ERR_UNSUPPORTED;
+  }
+  const int64_t st[] = {s->q_stride_b, s->q_stride_t, s->q_stride_h, s->kv_stride_b, s->kv_stride_t,
+                        s->kv_stride_h, s->o_stride_b, s->o_stride_t, s->o_stride_h};
+  for (int64_t x : st)
+    if (x < 0 || (x % 8)) {
+      set_err("strides must be non-negative multiples of 8 elements (got %lld)", (long long)x);
+      return SP_ERR_INVALID_ARG;
+    }
+  if (s->q_stride_t < s->head_dim || s->kv_stride_t < s->head_dim || s->o_stride_t < s->head_dim ||
+      (s->q_stride_h < s->head_dim && s->n_q_heads > 1) || (s->kv_stride_h < s->head_dim && s->n_kv_heads > 1) ||
+      (s->o_stride_h < s->head_dim && s->n_q_heads > 1)) {
+    set_err("token/head strides smaller than head_dim");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (!(s->softmax_scale >= 0.f) || std::isinf(s->softmax_scale)) {
+    set_err("softmax_scale must be finite and >= 0 (0 selects 1/sqrt(head_dim))");
+    return SP_ERR_INVALID_ARG;
+  }
+  return SP_OK;
+}
+
+size_t pack_bytes(const sp_shape *s) {
+  return align_up((size_t)s->batch * s->n_kv_heads * s->seq * s->head_dim * 2 * 2, 256);
+}
+size_t lws_bytes(const sp_shape *s, int n_dense) {
+  const size_t nqb = s->seq / s->block;
+  return align_up((size_t)s->batch * n_dense * nqb * nqb * s->block * sizeof(float), 256);
+}
+
+sp_status check_ptr16(const void *p, const char *name) {
+  if (!p) {
+    set_err("%s is NULL", name);
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((uintptr_t)p % 16) {
+    set_err("%s is not 16-byte aligned", name);
+    return SP_ERR_INVALID_ARG;
+  }
+  return SP_OK;
+}
+
+sp_status check_heads(const sp_shape *s, const int32_t *ids, int n, const char *name) {
+  if (!ids) {
+    set_err("%s is NULL", name);
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n <= 0 || n > s->n_q_heads) {
+    set_err("number of listed heads %d outside [1, %d]", n, s->n_q_heads);
+    return SP_ERR_INVALID_ARG;
+  }
+  bool seen[SP_MAX_HEADS] = {false};
+  for (int a = 0; a < n; ++a) {
+    if (ids[a] < 0 || ids[a] >= s->n_q_heads) {
+      set_err("%s[%d] = %d outside [0, %d)", name, a, ids[a], s->n_q_heads);
+      return SP_ERR_INVALID_ARG;
+    }
+    if (seen[ids[a]]) {
+      set_err("%s lists head %d twice", name, ids[a]);
+      return SP_ERR_INVALID_ARG;
+    }
+    seen[ids[a]] = true;
+  }
+  return SP_OK;
+}
+
+sp_status hip_check(hipError_t e, const char *what) {
+  if (e != hipSuccess) {
+    set_err("%s: %s", what, hipGetErrorString(e));
+    return SP_ERR_HIP;
+  }
+  return SP_OK;
+}
+
+sp_status launch_pack(const sp_shape *s, const void *k, const void *v, void *ws, hipStream_t st) {
+  PackParams pp;
+  pp.k = (const uint16_t *)k;
+  pp.v = (const uint16_t *)v;
+  pp.out = (char *)ws;
+  pp.sb = s->kv_stride_b;
+  pp.st = s->kv_stride_t;
+  pp.sh = s->kv_stride_h;
+  pp.n_kv_heads = s->n_kv_heads;
+  pp.n_sub = s->seq / KT;
+  dim3 grid(s->seq / KT, s->n_kv_heads, s->batch);
+  if (s->head_dim == 128)
+    hipLaunchKernelGGL(pack_kv_kernel<128>, grid, dim3(256), 0, st, pp);
+  else
+    hipLaunchKernelGGL(pack_kv_kernel<64>, grid, dim3(256), 0, st, pp);
+  return hip_check(hipGetLastError(), "pack_kv_kernel launch");
+}
+
+void fill_attn(AttnParams &ap, const sp_shape *s, const void *q, const void *kvp, void *o) {
+  memset(&ap, 0, sizeof(ap));
+  ap.q = (const uint16_t *)q;
+  ap.kvp = (const char *)kvp;
+  ap.o = (uint16_t *)o;
+  ap.q_sb = s->q_stride_b;
+  ap.q_st = s->q_stride_t;
+  ap.q_sh = s->q_stride_h;
+  ap.o_sb = s->o_stride_b;
+  ap.o_st = s->o_stride_t;
+  ap.o_sh = s->o_stride_h;
+  ap.seq = s->seq;
+  ap.nqb = s->seq / s->block;
+  ap.n_kv_heads = s->n_kv_heads;
+  ap.group = s->n_q_heads / s->n_kv_heads;
+  const float scale = (s->softmax_scale > 0.f) ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
+  ap.c = scale * 1.4426950408889634f;
+}
+
+template <bool DENSE>
+sp_status launch_attn(const sp_shape *s, const AttnParams &ap, hipStream_t st) {
+  const int64_t nwg = (int64_t)s->batch * ap.n_heads * ap.nqb;
+  if (nwg <= 0 || nwg > 0x7FFFFFFF) {
+    set_err("grid too large");
+    return SP_ERR_UNSUPPORTED;
+  }
+  dim3 grid((unsigned)nwg);
+  if (s->head_dim == 128 && s->block == 128)
+    hipLaunchKernelGGL((attn_kernel<128, 128, DENSE>), grid, dim3(256), 0, st, ap);
+  else if (s->head_dim == 128 && s->block == 64)
+    hipLaunchKernelGGL((attn_kernel<128, 64, DENSE>), grid, dim3(128), 0, st, ap);
+  else if (s->head_dim == 64 && s->block == 128)
+    hipLaunchKernelGGL((attn_kernel<64, 128, DENSE>), grid, dim3(256), 0, st, ap);
+  else
+    hipLaunchKernelGGL((attn_kernel<64, 64, DENSE>), grid, dim3(128), 0, st, ap);
+  return hip_check(hipGetLastError(), DENSE ? "dense attn_kernel launch" : "sparse attn_kernel launch");
+}
+
+sp_status launch_mask(const float *scores, int n_maps, int nqb, int nkb, float gamma, int32_t *kb_idx,
+                      int32_t *kb_cnt, uint64_t *bitmask, hipStream_t st) {
+  const uint32_t gq = (uint32_t)rintf(gamma * 16777216.f);
+  const int64_t rows = (int64_t)n_maps * nqb;
+  dim3 grid((unsigned)((rows + 3) / 4));
+  if (nkb <= 256)
+    hipLaunchKernelGGL(mask_kernel<4>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask);
+  else if (nkb <= 1024)
+    hipLaunchKernelGGL(mask_kernel<16>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask);
+  else
+    hipLaunchKernelGGL(mask_kernel<0>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask);
+  return hip_check(hipGetLastError(), "mask_kernel launch");
+}
+
+sp_status check_ws(const void *ws, size_t have, size_t need) {
+  if (need == 0) return SP_OK;
+  if (!ws) {
+    set_err("workspace is NULL (%zu bytes needed)", need);
+    return SP_ERR_WORKSPACE;
+  }
+  if ((uintptr_t)ws % 256) {
+    set_err("workspace is not 256-byte aligned");
+    return SP_ERR_WORKSPACE;
+  }
+  if (have < need) {
+    set_err("workspace too small: %zu bytes given, %zu needed", have, need);
+    return SP_ERR_WORKSPACE;
+  }
+  return SP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *sp_status_string(sp_status s) {
+  switch (s) {
+    case SP_OK: return "SP_OK";
+    case SP_ERR_INVALID_ARG: return "SP_ERR_INVALID_ARG";
+    case SP_ERR_UNSUPPORTED: return "SP_ERR_UNSUPPORTED";
+    case SP_ERR_WORKSPACE: return "SP_ERR_WORKSPACE";
+    case SP_ERR_HIP: return "SP_ERR_HIP";
+  }
+  return "SP_ERR_UNKNOWN";
+}
+
+const char *sp_last_error(void) { return g_err; }
+
+sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_t *bytes) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if (!bytes) {
+    set_err("bytes is NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n_dense_heads < 0 || n_dense_heads > shape->n_q_heads) {
+    set_err("n_dense_heads %d outside [0, %d]", n_dense_heads, shape->n_q_heads);
+    return SP_ERR_INVALID_ARG;
+  }
+  *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads);
+  return SP_OK;
+}
+
+sp_status sp_dense_attn_with_block_scores(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                          const int32_t *head_ids, int32_t n_heads, void *o, float *block_scores,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k")) || (rc = check_ptr16(v, "v")) ||
+      (rc = check_ptr16(o, "o")))
+    return rc;
+  if ((rc = check_heads(shape, head_ids, n_heads, "head_ids"))) return rc;
+  if (block_scores && ((uintptr_t)block_scores % 4)) {
+    set_err("block_scores is misaligned");
+    return SP_ERR_INVALID_ARG;
+  }
+  const size_t need = pack_bytes(shape) + (block_scores ? lws_bytes(shape, n_heads) : 0);
+  if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
+  AttnParams ap;
+  fill_attn(ap, shape, q, workspace, o);
+  ap.n_heads = n_heads;
+  for (int a = 0; a < n_heads; ++a) ap.head_ids[a] = head_ids[a];
+  ap.lws = block_scores ? (float *)((char *)workspace + pack_bytes(shape)) : nullptr;
+  ap.scores = block_scores;
+  return launch_attn<true>(shape, ap, st);
+}
+
+sp_status sp_build_block_mask(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb, float gamma,
+                              int32_t *kb_idx, int32_t *kb_cnt, uint64_t *bitmask, void *hip_stream) {
+  g_err[0] = 0;
+  if (!block_scores || !kb_idx || !kb_cnt) {
+    set_err("block_scores / kb_idx / kb_cnt must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n_maps <= 0 || nqb <= 0 || nkb <= 0) {
+    set_err("n_maps, nqb, nkb must be positive");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (nqb != nkb) {
+    set_err("nqb (%d) != nkb (%d): causal prefill maps are square", nqb, nkb);
+    return SP_ERR_INVALID_ARG;
+  }
+  if (nkb > 32768) {
+    set_err("nkb %d exceeds 32768", nkb);
+    return SP_ERR_UNSUPPORTED;
+  }
+  if (!(gamma > 0.f) || gamma > 1.f) {
+    set_err("gamma %g outside (0, 1]", (double)gamma);
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((int64_t)n_maps * nqb > 0x7FFFFFF0ll) {
+    set_err("too many rows");
+    return SP_ERR_UNSUPPORTED;
+  }
+  return launch_mask(block_scores, n_maps, nqb, nkb, gamma, kb_idx, kb_cnt, bitmask, (hipStream_t)hip_stream);
+}
+
+sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void *k, const void *v,
+                               const int32_t *head_ids, const int32_t *head_map, int32_t n_heads,
+                               const int32_t *kb_idx, const int32_t *kb_cnt, int32_t n_maps, void *o,
+                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k")) || (rc = check_ptr16(v, "v")) ||
+      (rc = check_ptr16(o, "o")))
+    return rc;
+  if ((rc = check_heads(shape, head_ids, n_heads, "head_ids"))) return rc;
+  if (!head_map || !kb_idx || !kb_cnt) {
+    set_err("head_map / kb_idx / kb_cnt must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n_maps <= 0) {
+    set_err("n_maps must be positive");
+    return SP_ERR_INVALID_ARG;
+  }
+  for (int a = 0; a < n_heads; ++a)
+    if (head_map[a] < 0 || head_map[a] >= n_maps) {
+      set_err("head_map[%d] = %d outside [0, %d)", a, head_map[a], n_maps);
+      return SP_ERR_INVALID_ARG;
+    }
+  if ((rc = check_ws(workspace, workspace_bytes, pack_bytes(shape)))) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
+  AttnParams ap;
+  fill_attn(ap, shape, q, workspace, o);
+  ap.n_heads = n_heads;
+  ap.n_maps = n_maps;
+  for (int a = 0; a < n_heads; ++a) {
+    ap.head_ids[a] = head_ids[a];
+    ap.head_map[a] = head_map[a];
+  }
+  ap.kb_idx = kb_idx;
+  ap.kb_cnt = kb_cnt;
+  return launch_attn<false>(shape, ap, st);
+}
+
+sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
+                           const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                           float gamma, void *o, float *block_scores, int32_t *kb_idx, int32_t *kb_cnt,
+                           void *workspace, size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k")) || (rc = check_ptr16(v, "v")) ||
+      (rc = check_ptr16(o, "o")))
+    return rc;
+  if (!head_to_cluster || !pivot_heads || !block_scores || !kb_idx || !kb_cnt) {
+    set_err("head_to_cluster / pivot_heads / block_scores / kb_idx / kb_cnt must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  const int Hq = shape->n_q_heads;
+  if (n_clusters <= 0 || n_clusters > Hq) {
+    set_err("n_clusters %d outside [1, %d]", n_clusters, Hq);
+    return SP_ERR_INVALID_ARG;
+  }
+  if (!(gamma > 0.f) || gamma > 1.f) {
+    set_err("gamma %g outside (0, 1]", (double)gamma);
+    return SP_ERR_INVALID_ARG;
+  }
+  bool is_pivot[SP_MAX_HEADS] = {false};
+  for (int hq = 0; hq < Hq; ++hq)
+    if (head_to_cluster[hq] < -1 || head_to_cluster[hq] >= n_clusters) {
+      set_err("head_to_cluster[%d] = %d outside [-1, %d)", hq, head_to_cluster[hq], n_clusters);
+      return SP_ERR_INVALID_ARG;
+    }
+  for (int c = 0; c < n_clusters; ++c) {
+    const int ph = pivot_heads[c];
+    if (ph < 0 || ph >= Hq) {
+      set_err("pivot_heads[%d] = %d outside [0, %d)", c, ph, Hq);
+      return SP_ERR_INVALID_ARG;
+    }
+    if (head_to_cluster[ph] != c) {
+      set_err("pivot_heads[%d] = %d lies in cluster %d", c, ph, head_to_cluster[ph]);
+      return SP_ERR_INVALID_ARG;
+    }
+    is_pivot[ph] = true;
+  }
+  const size_t need = pack_bytes(shape) + lws_bytes(shape, n_clusters);
+  if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int nqb = shape->seq / shape->block;
+
+  if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
+  // 1. pivots: dense attention + block-mass scores (Alg. 1 line 8 with M = ones, Alg. 4)
+  AttnParams ap;
+  fill_attn(ap, shape, q, workspace, o);
+  ap.n_heads = n_clusters;
+  for (int c = 0; c < n_clusters; ++c) ap.head_ids[c] = pivot_heads[c];
+  ap.lws = (float *)((char *)workspace + pack_bytes(shape));
+  ap.scores = block_scores;
+  if ((rc = launch_attn<true>(shape, ap, st))) return rc;
+  // 2. heads outside every cluster: dense, no scores
+  int n_free = 0;
+  fill_attn(ap, shape, q, workspace, o);
+  for (int hq = 0; hq < Hq; ++hq)
+    if (head_to_cluster[hq] < 0) ap.head_ids[n_free++] = hq;
+  if (n_free) {
+    ap.n_heads = n_free;
+    if ((rc = launch_attn<true>(shape, ap, st))) return rc;
+  }
+  // 3. one pattern per (batch, cluster) (Alg. 2)
+  if ((rc = launch_mask(block_scores, shape->batch * n_clusters, nqb, nqb, gamma, kb_idx, kb_cnt, nullptr, st)))
+    return rc;
+  // 4. remaining heads share their cluster's pattern (Alg. 4) and run block-sparse (Sec. 5.1)
+  int n_sparse = 0;
+  fill_attn(ap, shape, q, workspace, o);
+  for (int hq = 0; hq < Hq; ++hq)
+    if (head_to_cluster[hq] >= 0 && !is_pivot[hq]) {
+      ap.head_ids[n_sparse] = hq;
+      ap.head_map[n_sparse] = head_to_cluster[hq];
+      ++n_sparse;
+    }
+  if (n_sparse) {
+    ap.n_heads = n_sparse;
+    ap.n_maps = n_clusters;
+    ap.kb_idx = kb_idx;
+    ap.kb_cnt = kb_cnt;
+    if ((rc = launch_attn<false>(shape, ap, st))) return rc;
+  }
+  return SP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,113 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the
+header declares, and rejects bad arguments synchronously without a GPU."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _shape(sp, **kw):
+    s = sp.SpShape()
+    s.batch, s.seq, s.n_q_heads, s.n_kv_heads, s.head_dim, s.block = 1, 1024, 4, 4, 64, 64
+    for f in ("q", "kv", "o"):
+        setattr(s, f + "_stride_b", 1024 * 256)
+        setattr(s, f + "_stride_t", 256)
+        setattr(s, f + "_stride_h", 64)
+    for k, v in kw.items():
+        setattr(s, k, v)
+    return s
+
+
+def test_header_symbols_are_exported():
+    import paper_2505_19578_amd as sp
+    hdr = open(os.path.join(ROOT, "include", "shareprefill.h")).read()
+    declared = set(re.findall(r"\b(sp_[a-z_]+)\s*\(", hdr))
+    assert declared == set(sp.EXPORTED_SYMBOLS)
+    L = sp.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.sp_status_string(0) == b"SP_OK"
+
+
+def test_workspace_bytes_and_shape_validation():
+    import paper_2505_19578_amd as sp
+    s = _shape(sp)
+    pack = 1 * 4 * 1024 * 64 * 2 * 2
+    assert sp.sp_workspace_bytes(s, 0) == pack
+    assert sp.sp_workspace_bytes(s, 2) == pack + 2 * 16 * 16 * 64 * 4
+    for bad, status in [
+        (dict(seq=1000), "SP_ERR_UNSUPPORTED"),
+        (dict(head_dim=96), "SP_ERR_UNSUPPORTED"),
+        (dict(block=32), "SP_ERR_UNSUPPORTED"),
+        (dict(n_kv_heads=3), "SP_ERR_INVALID_ARG"),
+        (dict(q_stride_t=260), "SP_ERR_INVALID_ARG"),
+        (dict(batch=0), "SP_ERR_INVALID_ARG"),
+        (dict(softmax_scale=-1.0), "SP_ERR_INVALID_ARG"),
+    ]:
+        with pytest.raises(sp.SpError) as e:
+            sp.sp_workspace_bytes(_shape(sp, **bad), 1)
+        assert e.value.status_name == status, bad
+    with pytest.raises(sp.SpError):
+        sp.sp_workspace_bytes(s, 5)
+
+
+def test_calls_reject_bad_arguments_without_launching():
+    """Null / misaligned pointers, bad ids, bad gamma, missing workspace: all rejected on the host."""
+    import ctypes
+    import paper_2505_19578_amd as sp
+    L = sp.lib()
+    s = _shape(sp)
+    ids = (ctypes.c_int32 * 4)(0, 1, 2, 3)
+    fake = ctypes.c_void_p(4096)     # never dereferenced: validation fails first
+    rc = L.sp_dense_attn_with_block_scores(ctypes.byref(s), None, fake, fake, ids, 1, fake, None, None, 0, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"q is NULL" in L.sp_last_error()
+    rc = L.sp_dense_attn_with_block_scores(ctypes.byref(s), ctypes.c_void_p(4100), fake, fake, ids, 1, fake, None,
+                                           None, 0, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    rc = L.sp_dense_attn_with_block_scores(ctypes.byref(s), fake, fake, fake, ids, 1, fake, None, None, 0, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    bad = (ctypes.c_int32 * 2)(1, 1)
+    rc = L.sp_dense_attn_with_block_scores(ctypes.byref(s), fake, fake, fake, bad, 2, fake, None, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"twice" in L.sp_last_error()
+    rc = L.sp_build_block_mask(fake, 1, 16, 16, ctypes.c_float(0.0), fake, fake, None, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    rc = L.sp_build_block_mask(fake, 1, 16, 8, ctypes.c_float(0.9), fake, fake, None, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    rc = L.sp_build_block_mask(fake, 1, 40000, 40000, ctypes.c_float(0.9), fake, fake, None, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_UNSUPPORTED"
+    hm = (ctypes.c_int32 * 1)(3)
+    rc = L.sp_block_sparse_attn(ctypes.byref(s), fake, fake, fake, ids, hm, 1, fake, fake, 2, fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"head_map" in L.sp_last_error()
+    h2c = (ctypes.c_int32 * 4)(0, 0, 1, 1)
+    piv = (ctypes.c_int32 * 2)(0, 1)     # head 1 is not in cluster 1
+    rc = L.sp_prefill_layer(ctypes.byref(s), fake, fake, fake, h2c, piv, 2, ctypes.c_float(0.9), fake, fake, fake,
+                            fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"lies in cluster" in L.sp_last_error()
+    piv = (ctypes.c_int32 * 2)(0, 2)
+    rc = L.sp_prefill_layer(ctypes.byref(s), fake, fake, fake, h2c, piv, 2, ctypes.c_float(0.9), fake, fake, fake,
+                            fake, fake, 16, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+
+
+def test_generator_is_deterministic_and_bf16_round_trip():
+    import numpy as np
+    from synth import CONFIGS, make_layer, f32_to_bf16_bits, bf16_bits_to_f32
+    a = make_layer(CONFIGS["tiny"], seq=256)
+    b = make_layer(CONFIGS["tiny"], seq=256)
+    for x in "qkv":
+        assert np.array_equal(a[x], b[x])
+    assert list(a["head_to_cluster"]) == [0, 0, 1, 1] and list(a["pivot_heads"]) == [0, 2]
+    c = make_layer(CONFIGS["tiny"], layer=1, seq=256)
+    assert not np.array_equal(a["q"], c["q"])
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.0e38], dtype=np.float32)
+    bits = f32_to_bf16_bits(x)
+    # 1 + 2^-8 is a tie -> even (1.0); 1 + 3*2^-8 is a tie -> even (1 + 2^-6)
+    assert list(bf16_bits_to_f32(bits)[:4]) == [1.0, 1.0, 1.015625, -2.5]
+    import torch
+    t = torch.tensor(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(bits, t)
+    q = make_layer(CONFIGS["qwen7b_128k"], seq=512)
+    assert sorted(np.bincount(q["head_to_cluster"])) == [4] * 7
+    assert all(q["head_to_cluster"][p] == c for c, p in enumerate(q["pivot_heads"]))
