@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the SharePrefill per-layer prefill attention path on one MI355X.
+
+A "step" is one fused sp_prefill_layer call (K/V packing -> dense pivots + block
+scores -> mask builder -> block-sparse heads) on one layer of seeded synthetic
+input that is already resident in HBM.  Prints ONE JSON line.
+
+  value        effective TFLOP/s = flops a dense causal layer would need / time of the
+               sparse-prefill layer (so it grows with both kernel speed and sparsity)
+  ms_per_step  sparse-prefill attention ms per layer
+  roofline     dense-pivot kernel (the dominant one): tiles x 4*B^2*d flops / its average
+               launch time (HIP events recorded by the library on the launch stream)
+               against the bf16 dense MFMA peak
+  cpu_baseline the CPU oracle timed on a bounded sample of query-block rows of the same
+               workload, in the same unit
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="llama8b_128k")
+    ap.add_argument("--seq", type=int, default=None, help="override the sequence length (debug)")
+    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense-all", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size reference for HBM counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2505_19578_amd as sp
+    from synth import CONFIGS, make_layer
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    t0 = time.time()
+    L = make_layer(CONFIGS[args.config], layer=args.layer, seq=args.seq)
+    cfg = L["cfg"]
+    gen_s = time.time() - t0
+    dev = {x: torch.from_numpy(L[x].view(np.int16)).view(torch.bfloat16).unsqueeze(0).cuda() for x in "qkv"}
+    q, k, v = dev["q"], dev["k"], dev["v"]
+    B, d, N, Hq = cfg.block, cfg.head_dim, cfg.seq, cfg.n_q_heads
+    nqb = N // B
+    C = cfg.n_clusters
+    h2c, piv = [int(x) for x in L["head_to_cluster"]], [int(x) for x in L["pivot_heads"]]
+    shape = sp.shape_of(q, k, None, B)
+    o = torch.zeros_like(q)
+    ws = torch.empty(sp.sp_workspace_bytes(shape, C), dtype=torch.uint8, device="cuda")
+    scores = torch.empty((1, C, nqb, nqb), dtype=torch.float32, device="cuda")
+    kb_idx = torch.empty((1, C, nqb, nqb), dtype=torch.int32, device="cuda")
+    kb_cnt = torch.empty((1, C, nqb), dtype=torch.int32, device="cuda")
+
+    def step():
+        sp.sp_prefill_layer(shape, q, k, v, h2c, piv, cfg.gamma, o, scores, kb_idx, kb_cnt, ws)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sp.sp_profile_enable(True)
+    sp.sp_profile_read(reset=True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = sp.sp_profile_read(reset=True)
+    sp.sp_profile_enable(False)
+    ms_step = wall * 1e3 / args.steps
+
+    # work actually done
+    cnt = kb_cnt.cpu().numpy()[0].astype(np.int64)            # [C][nqb]
+    tile_flops = 4.0 * B * B * d
+    n_sparse_heads = sum(1 for h in range(Hq) if h2c[h] >= 0 and h not in piv)
+    n_free = sum(1 for h in range(Hq) if h2c[h] < 0)
+    dense_tiles_per_head = nqb * (nqb + 1) // 2
+    pivot_tiles = (C + n_free) * dense_tiles_per_head
+    sparse_tiles = int(sum(cnt[h2c[h]].sum() for h in range(Hq) if h2c[h] >= 0 and h not in piv))
+    density = float(cnt.sum() / (C * dense_tiles_per_head))
+    dense_equiv_flops = Hq * 4.0 * d * (N * (N + 1) / 2.0)    # exact causal pair count
+    computed_flops = (pivot_tiles + sparse_tiles) * tile_flops
+
+    # dominant kernel: dense pivots
+    dense_ms, dense_n = prof["dense"]
+    dense_avg_ms = dense_ms / max(dense_n, 1)
+    dense_flops_per_launch = pivot_tiles * tile_flops if n_free == 0 else C * dense_tiles_per_head * tile_flops
+    if n_free:
+        dense_avg_ms = dense_ms / args.steps          # two dense launches per step: report them together
+        dense_flops_per_launch = pivot_tiles * tile_flops
+    dense_tflops = dense_flops_per_launch / (dense_avg_ms * 1e-3) / 1e12 if dense_avg_ms > 0 else 0.0
+    sparse_ms, sparse_n = prof["sparse"]
+    sparse_avg_ms = sparse_ms / max(sparse_n, 1)
+    sparse_tflops = sparse_tiles * tile_flops / (sparse_avg_ms * 1e-3) / 1e12 if sparse_avg_ms > 0 else 0.0
+
+    # the "vs dense" denominator: this library's own dense kernel on every head, no scores
+    dense_all_ms = None
+    if not args.no_dense_all:
+        heads = list(range(Hq))
+        sp.sp_dense_attn_with_block_scores(shape, q, k, v, heads, o, None, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 2
+        for _ in range(reps):
+            sp.sp_dense_attn_with_block_scores(shape, q, k, v, heads, o, None, ws)
+        torch.cuda.synchronize()
+        dense_all_ms = (time.perf_counter() - t0) * 1e3 / reps
+
+    out = {
+        "metric": "sparse-prefill attention ms/layer at 128K + effective TFLOP/s vs dense",
+        "value": dense_equiv_flops / (ms_step * 1e-3) / 1e12,
+        "unit": "effective TFLOP/s (dense-causal-equivalent flops / sparse-prefill layer time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: 1 layer, batch 1, {Hq}q/{cfg.n_kv_heads}kv heads, d{d}, "
+                               f"seq {N}, block {B}, {C} clusters x {cfg.cluster_size} heads, "
+                               f"1 pivot each, gamma {cfg.gamma}",
+                   "seed": L["seed"], "density": density},
+        "ms_per_layer": ms_step,
+        "computed_tflops": computed_flops / (ms_step * 1e-3) / 1e12,
+        "computed_frac_of_bf16_peak": computed_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "tiles": {"pivot": int(pivot_tiles), "sparse": int(sparse_tiles),
+                  "dense_layer": int(Hq * dense_tiles_per_head)},
+        "kernel_ms": {kk: (prof[kk][0] / max(prof[kk][1], 1)) for kk in prof},
+        "sparse_kernel_tflops": sparse_tflops,
+        "dense_all_heads_ms": dense_all_ms,
+        "speedup_vs_dense": (dense_all_ms / ms_step) if dense_all_ms else None,
+        "roofline": {"kernel": "attn_kernel<dense> (pivot heads + block scores)", "bound": "mfma",
+                     "achieved": dense_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": dense_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launch_ms": dense_avg_ms},
+        "input_gen_s": gen_s,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        from synth import bf16_bits_to_f32
+        rows = sorted({nqb // 4, nqb // 2}) if nqb >= 8 else [nqb - 1]
+        # bounded sample: every head, a couple of mid-length query-block rows
+        idx_h, cnt_h = kb_idx.cpu().numpy()[0], kb_cnt.cpu().numpy()[0]
+        hq = bf16_bits_to_f32(L["q"][: (max(rows) + 1) * B])
+        hk = bf16_bits_to_f32(L["k"][: (max(rows) + 1) * B])
+        hv = bf16_bits_to_f32(L["v"][: (max(rows) + 1) * B])
+        t0 = time.perf_counter()
+        oracle.prefill_layer(hq, hk, hv, B, h2c, piv, cfg.gamma, rows=rows)
+        cpu_s = time.perf_counter() - t0
+        pairs = sum(B * (i * B) + B * (B + 1) / 2 for i in rows)
+        cpu_equiv = Hq * 4.0 * d * pairs
+        out["cpu_baseline"] = {
+            "value": cpu_equiv / cpu_s / 1e12, "unit": out["unit"], "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": cpu_s,
+            "sample": f"all {Hq} heads, query-block rows {rows} of {nqb} (sequence prefix of "
+                      f"{(max(rows) + 1) * B} tokens), same inputs",
+        }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -58,6 +58,18 @@ const char *sp_status_string(sp_status s);
 const char *sp_last_error(void);
 
 /*
+ * Optional per-kernel timing for benchmarks (no counterpart in the paper; its protocol,
+ * App. A.2 "Latency Benchmark", times whole runs).  While enabled, every kernel the calls
+ * below launch is bracketed by two HIP events on the caller's stream.  After the caller has
+ * synchronised that stream, sp_profile_read sums elapsed milliseconds and launch counts per
+ * kernel kind into host arrays ms[4] / launches[4]: 0 = K/V packing, 1 = dense attention
+ * (+ scores), 2 = mask builder, 3 = block-sparse attention; `reset` != 0 drops the records.
+ * Process-wide and not thread-safe.
+ */
+sp_status sp_profile_enable(int32_t on);
+sp_status sp_profile_read(float *ms, int32_t *launches, int32_t reset);
+
+/*
  * Bytes of device workspace needed by the calls below for this shape when at most
  * `n_dense_heads` heads per batch entry run dense attention *with* block scores in
  * one call (0 if no scores are ever requested).

@@ -6,10 +6,10 @@ Python binding with the same entry-point names.  PyTorch is used only for
 device memory and streams.  There is no CPU fallback: without the compiled
 library (or without a GPU for the compute calls) the calls raise.
 """
-from .binding import (SpError, SpShape, lib, shape_of, sp_workspace_bytes,
+from .binding import (SpError, SpShape, lib, shape_of, sp_workspace_bytes, sp_profile_enable, sp_profile_read,
                       sp_dense_attn_with_block_scores, sp_build_block_mask,
                       sp_block_sparse_attn, sp_prefill_layer, EXPORTED_SYMBOLS)
 
-__all__ = ["SpError", "SpShape", "lib", "shape_of", "sp_workspace_bytes",
+__all__ = ["SpError", "SpShape", "lib", "shape_of", "sp_workspace_bytes", "sp_profile_enable", "sp_profile_read",
            "sp_dense_attn_with_block_scores", "sp_build_block_mask",
            "sp_block_sparse_attn", "sp_prefill_layer", "EXPORTED_SYMBOLS"]

@@ -12,7 +12,7 @@ from typing import Optional, Sequence
 from .build import library_path
 
 EXPORTED_SYMBOLS = [
-    "sp_status_string", "sp_last_error", "sp_workspace_bytes",
+    "sp_status_string", "sp_last_error", "sp_profile_enable", "sp_profile_read", "sp_workspace_bytes",
     "sp_dense_attn_with_block_scores", "sp_build_block_mask",
     "sp_block_sparse_attn", "sp_prefill_layer",
 ]
@@ -51,6 +51,10 @@ def lib() -> ctypes.CDLL:
         L.sp_status_string.argtypes = [ctypes.c_int]
         L.sp_last_error.restype = ctypes.c_char_p
         L.sp_last_error.argtypes = []
+        L.sp_profile_enable.restype = ctypes.c_int
+        L.sp_profile_enable.argtypes = [ctypes.c_int32]
+        L.sp_profile_read.restype = ctypes.c_int
+        L.sp_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ip, ctypes.c_int32]
         L.sp_workspace_bytes.restype = ctypes.c_int
         L.sp_workspace_bytes.argtypes = [sp, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
         L.sp_dense_attn_with_block_scores.restype = ctypes.c_int
@@ -102,6 +106,21 @@ def shape_of(q, k, o=None, block: int = 128, softmax_scale: float = 0.0) -> SpSh
     s.o_stride_b, s.o_stride_t, s.o_stride_h = o.stride(0), o.stride(1), o.stride(2)
     s.softmax_scale = softmax_scale
     return s
+
+
+KERNEL_KINDS = ("pack", "dense", "mask", "sparse")
+
+
+def sp_profile_enable(on: bool):
+    _check(lib().sp_profile_enable(1 if on else 0))
+
+
+def sp_profile_read(reset: bool = True):
+    """{kind: (total ms, launches)} since the last reset; synchronise the stream first."""
+    ms = (ctypes.c_float * 4)()
+    n = (ctypes.c_int32 * 4)()
+    _check(lib().sp_profile_read(ms, n, 1 if reset else 0))
+    return {k: (float(ms[a]), int(n[a])) for a, k in enumerate(KERNEL_KINDS)}
 
 
 def sp_workspace_bytes(shape: SpShape, n_dense_heads: int) -> int:

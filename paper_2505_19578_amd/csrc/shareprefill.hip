@@ -28,6 +28,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "shareprefill.h"
 
@@ -44,6 +45,36 @@ constexpr int SP_MAX_HEADS = 128;
 constexpr int KT = 64;  // keys per sub-tile
 
 thread_local char g_err[512] = "";
+
+// Optional per-kernel timing (sp_profile_enable / sp_profile_read): every launch is bracketed
+// by two HIP events on the caller's stream.  Process-wide, not thread-safe; meant for benches.
+enum KernelKind { KK_PACK = 0, KK_DENSE = 1, KK_MASK = 2, KK_SPARSE = 3, KK_COUNT = 4 };
+struct ProfRec {
+  int kind;
+  hipEvent_t e0, e1;
+};
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+
+struct ProfScope {
+  hipStream_t st;
+  bool on;
+  ProfRec rec;
+  ProfScope(int kind, hipStream_t s) : st(s), on(g_prof_on) {
+    if (!on) return;
+    rec.kind = kind;
+    if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) {
+      on = false;
+      return;
+    }
+    (void)hipEventRecord(rec.e0, st);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(rec.e1, st);
+    g_prof.push_back(rec);
+  }
+};
 
 void set_err(const char *fmt, ...) {
   va_list ap;
@@ -553,6 +584,7 @@ sp_status launch_pack(const sp_shape *s, const void *k, const void *v, void *ws,
   pp.n_kv_heads = s->n_kv_heads;
   pp.n_sub = s->seq / KT;
   dim3 grid(s->seq / KT, s->n_kv_heads, s->batch);
+  ProfScope prof(KK_PACK, st);
   if (s->head_dim == 128)
     hipLaunchKernelGGL(pack_kv_kernel<128>, grid, dim3(256), 0, st, pp);
   else
@@ -587,6 +619,7 @@ sp_status launch_attn(const sp_shape *s, const AttnParams &ap, hipStream_t st) {
     return SP_ERR_UNSUPPORTED;
   }
   dim3 grid((unsigned)nwg);
+  ProfScope prof(DENSE ? KK_DENSE : KK_SPARSE, st);
   if (s->head_dim == 128 && s->block == 128)
     hipLaunchKernelGGL((attn_kernel<128, 128, DENSE>), grid, dim3(256), 0, st, ap);
   else if (s->head_dim == 128 && s->block == 64)
@@ -603,6 +636,7 @@ sp_status launch_mask(const float *scores, int n_maps, int nqb, int nkb, float g
   const uint32_t gq = (uint32_t)rintf(gamma * 16777216.f);
   const int64_t rows = (int64_t)n_maps * nqb;
   dim3 grid((unsigned)((rows + 3) / 4));
+  ProfScope prof(KK_MASK, st);
   if (nkb <= 256)
     hipLaunchKernelGGL(mask_kernel<4>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask);
   else if (nkb <= 1024)
@@ -645,6 +679,42 @@ const char *sp_status_string(sp_status s) {
 }
 
 const char *sp_last_error(void) { return g_err; }
+
+sp_status sp_profile_enable(int32_t on) {
+  g_prof_on = on != 0;
+  return SP_OK;
+}
+
+sp_status sp_profile_read(float *ms, int32_t *launches, int32_t reset) {
+  g_err[0] = 0;
+  if (!ms || !launches) {
+    set_err("ms / launches must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  for (int a = 0; a < KK_COUNT; ++a) {
+    ms[a] = 0.f;
+    launches[a] = 0;
+  }
+  sp_status rc = SP_OK;
+  for (const ProfRec &r : g_prof) {
+    float t = 0.f;
+    const hipError_t e = hipEventElapsedTime(&t, r.e0, r.e1);
+    if (e != hipSuccess) {
+      rc = hip_check(e, "hipEventElapsedTime (synchronise the stream before sp_profile_read)");
+      break;
+    }
+    ms[r.kind] += t;
+    launches[r.kind] += 1;
+  }
+  if (reset && rc == SP_OK) {
+    for (const ProfRec &r : g_prof) {
+      (void)hipEventDestroy(r.e0);
+      (void)hipEventDestroy(r.e1);
+    }
+    g_prof.clear();
+  }
+  return rc;
+}
 
 sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_t *bytes) {
   g_err[0] = 0;
