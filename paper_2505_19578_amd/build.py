@@ -13,6 +13,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 instructions are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # device code never relies on NaN semantics (the score quantiser tests bits); lets fmax chains
+    # compile to v_max3 without a canonicalising v_max per operand
+    "-Xarch_device", "-fno-honor-nans",
     "-I" + os.path.join(ROOT, "include"),
 ]
 
@@ -29,6 +32,11 @@ def build_library(verbose: bool = False) -> str:
 
 
 def library_path(build_if_missing: bool = True) -> str:
+    override = os.environ.get("SHAREPREFILL_LIB")      # an explicitly chosen build of the same library
+    if override:
+        if not os.path.exists(override):
+            raise FileNotFoundError(override)
+        return override
     if not os.path.exists(LIB):
         if not build_if_missing:
             raise FileNotFoundError(LIB)

@@ -23,6 +23,7 @@
 // 4h+e for e<4, 8+4h+(e-4) for e>=4); pack_kv_kernel writes V in exactly that order.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdint>
@@ -45,6 +46,10 @@ constexpr int SP_MAX_HEADS = 128;
 constexpr int KT = 64;  // keys per sub-tile
 
 thread_local char g_err[512] = "";
+#ifdef DIAG_TIMING
+unsigned long long *g_dbg_store = nullptr;
+unsigned long long *g_dbg_ptr() { return g_dbg_store; }
+#endif
 
 // Optional per-kernel timing (sp_profile_enable / sp_profile_read): every launch is bracketed
 // by two HIP events on the caller's stream.  Process-wide, not thread-safe; meant for benches.
@@ -142,26 +147,59 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(PackParams p) {
 // ---------------------------------------------------------------------------------------------
 // attention kernel
 // ---------------------------------------------------------------------------------------------
+constexpr int SP_MAX_SLOTS = SP_MAX_HEADS + 8;
+// scheduler-hint knobs of the fast step (per MFMA: 1 LDS read and SGB_V VALU instructions)
+#ifndef SGB_N
+#define SGB_N 1
+#endif
+#ifndef SP_DK1
+#define SP_DK1 3
+#endif
+#ifndef SP_DV1
+#define SP_DV1 1
+#endif
+#ifndef SGB_PRE
+#define SGB_PRE 4
+#endif
+#ifndef SGB_V
+#define SGB_V 5
+#endif
+
 struct AttnParams {
   const uint16_t *q;
   const char *kvp;  // packed K/V images
   uint16_t *o;
   int64_t q_sb, q_st, q_sh, o_sb, o_st, o_sh;
   int seq, nqb, n_kv_heads, group, n_heads, n_maps;
-  float c;  // softmax scale * log2(e)
+  int ncol;   // slots per XCD: workgroup -> slot table below, 8 * ncol entries
+  int nrows;  // workgroup rows per slot (query blocks, or pairs of them)
+  float c;    // softmax scale * log2(e)
   float *lws;     // dense: block-local log2-sum-exp [b][n][nqb][nkb][B], or null
   float *scores;  // dense: [b][n][nqb][nkb], or null
   const int32_t *kb_idx;  // sparse: [b][n_maps][nqb][nkb]
   const int32_t *kb_cnt;  // sparse: [b][n_maps][nqb]
-  int32_t head_ids[SP_MAX_HEADS];
-  int32_t head_map[SP_MAX_HEADS];
+#ifdef DIAG_TIMING
+  unsigned long long *dbg;
+#endif
+  int32_t head_a[SP_MAX_SLOTS];    // query head of wave group 0, -1 = padding slot
+  int32_t head_b[SP_MAX_SLOTS];    // query head of wave group 1 (two-group kernels), -1 = none
+  int32_t head_map[SP_MAX_SLOTS];  // sparse: which list the slot's heads use
+  int32_t pos_a[SP_MAX_SLOTS];     // position of head_a in the caller's list (scores / lws index)
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-__device__ __forceinline__ float xor32(float x) {
-  return __shfl_xor(x, 32, 64);
+// max / sum of a value with its partner in lane ^ 32 (one v_permlane32_swap, no LDS round trip)
+__device__ __forceinline__ float max_xor32(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+__device__ __forceinline__ float sum_xor32(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -170,33 +208,89 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
-template <int D, int B, bool DENSE>
-__global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
-  constexpr int NW = B / 32;        // wavefronts per workgroup, 32 queries each
+// One wavefront-wide 1 KiB copy HBM/L2 -> LDS without passing through registers: lane l moves the
+// 16 bytes at g_uniform + lane_off to LDS byte address lds_base + 16 l (g_uniform, lds_base wave-uniform).  Issued from inline
+// assembly so that the compiler does not serialise it against the kernel's own LDS reads; the
+// kernel counts these loads itself (wait_vm).
+__device__ __forceinline__ void lds_dma16(const void *g_uniform, uint32_t lane_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(lane_off),
+               "s"(g_uniform)
+               : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Flash-attention sweep over 64-key sub-tiles t = 0 .. nsub-1, 32 queries per wavefront.
+//
+// Software pipeline (per wavefront), step t:
+//     MFMA stream   S[t+1] = K[t+1] Q^T          then   O += V[t]^T P[t]^T
+//     VALU stream   P[t] = 2^(S[t] c - m)        then   row max of S[t+1], running-max update
+//   interleaved instruction by instruction (scheduler hints), so the softmax runs in the shadow
+//   of the matrix pipe.  Steps near the diagonal take a general path (causal mask / skip).
+// K and V images ride in LDS rings (RK, RV slots) filled by LDS-direct loads issued DK resp. DV
+// steps ahead; one workgroup barrier per step.
+// NG = 1: one query block per workgroup (B/32 wavefronts), 2 workgroups per CU.
+// NG = 2: two wave groups share every K/V image: two consecutive query blocks of one head (dense)
+//         or one query block of two heads that use the same list (sparse); 1 workgroup per CU,
+//         deeper rings.
+template <int D, int B, int NG, bool DENSE, bool SCORES>
+__global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_kernel(AttnParams p) {
+  constexpr int NW = B / 32;        // wavefronts per group, 32 queries each
+  constexpr int NWT = NW * NG;      // wavefronts per workgroup
   constexpr int SPB = B / KT;       // sub-tiles per key block
   constexpr int IMG = KT * D * 2;   // bytes of a packed K (or V) image
-  constexpr int STAGE = 2 * IMG;    // K image + V image
+  constexpr int STAGE = 2 * IMG;    // K image + V image in the packed buffer
   constexpr int DS = D / 16;        // k-steps of the QK^T product
   constexpr int DB = D / 32;        // 32-row blocks of O^T
-  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
-  __shared__ float lse_sh[B];
+  constexpr int DK = NG == 2 ? 4 : SP_DK1, DV = NG == 2 ? 3 : SP_DV1;  // prefetch distances (steps)
+  constexpr int RK = DK, RV = DV + 1;                        // ring slots
+  constexpr int CH = IMG / 1024 / NWT;                       // 1 KiB chunks per wavefront per image
+  // loads that may still be in flight at the top of a step (each step issues CH for V, then CH for K)
+  constexpr int VM_KEEP = ((2 * DV - 1) < (2 * DK - 4) ? (2 * DV - 1) : (2 * DK - 4)) * CH;
+  static_assert(IMG % (1024 * NWT) == 0, "image must split evenly over the wavefronts");
+#ifndef SP_LDS_PAD
+#define SP_LDS_PAD 0
+#endif
+  __shared__ __attribute__((aligned(1024))) char smem[(RK + RV) * IMG + SP_LDS_PAD];
+  const uint32_t lds_k = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
+  const uint32_t lds_v = lds_k + RK * IMG;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, h = lane >> 5, c32 = lane & 31;
-  // workgroup -> (batch, listed head, query block): heads fastest, long rows first
-  int bid = blockIdx.x;
-  const int hslot = bid % p.n_heads;
-  bid /= p.n_heads;
-  const int i = p.nqb - 1 - (bid % p.nqb);
-  const int b = bid / p.nqb;
-  const int head = p.head_ids[hslot];
-  const int kvh = head / p.group;
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, c32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, kept scalar
+  const int g = w / NW, wg = w % NW;                        // wave group, wavefront inside the group
+  // workgroup -> (XCD, column, row, batch): workgroups are dealt round-robin to the 8 XCDs, so slot
+  // table row x lists the heads XCD x works on (heads that share a KV head sit on one XCD and meet in
+  // its L2); long rows first.
+  const int xcd = blockIdx.x & 7;
+  int rest = blockIdx.x >> 3;
+  const int slot = xcd * p.ncol + rest % p.ncol;
+  rest /= p.ncol;
+  const int row = p.nrows - 1 - (rest % p.nrows);
+  const int b = rest / p.nrows;
+  if (p.head_a[slot] < 0) return;
   const int nkb = p.nqb;
+  // this wave group's head and query block; idiag = the workgroup's last key block (dense)
+  const int head = (NG == 2 && !DENSE && g == 1) ? p.head_b[slot] : p.head_a[slot];
+  const int ib = (NG == 2 && DENSE) ? 2 * row + g : row;
+  const bool active = head >= 0 && ib < p.nqb;
+  const int hpos = p.pos_a[slot];
+  const int kvh = p.head_a[slot] / p.group;
 
-  const int tq = 32 * w + c32;  // this lane's query inside the block
-  const uint16_t *qp = p.q + (int64_t)b * p.q_sb + ((int64_t)i * B + tq) * p.q_st + (int64_t)head * p.q_sh + 8 * h;
+  const int tq = 32 * wg + c32;  // this lane's query inside the block
   bf16x8 qf[DS];
+  if (active) {
+    const uint16_t *qp =
+        p.q + (int64_t)b * p.q_sb + ((int64_t)ib * B + tq) * p.q_st + (int64_t)head * p.q_sh + 8 * h;
 #pragma unroll
-  for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
+    for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
+  } else {
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[ds][e] = (__bf16)0.f;
+  }
 
   f32x16 oacc[DB];
 #pragma unroll
@@ -208,160 +302,398 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   int nblk;
   const int32_t *list = nullptr;
   if (DENSE) {
-    nblk = i + 1;
+    nblk = (NG == 2) ? ((2 * row + 1 < p.nqb) ? 2 * row + 2 : 2 * row + 1) : row + 1;
   } else {
-    const int64_t row = ((int64_t)b * p.n_maps + p.head_map[hslot]) * p.nqb + i;
-    nblk = p.kb_cnt[row];
+    const int64_t lrow_id = ((int64_t)b * p.n_maps + p.head_map[slot]) * p.nqb + row;
+    nblk = p.kb_cnt[lrow_id];
     nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
-    list = p.kb_idx + row * nkb;
+    list = p.kb_idx + lrow_id * nkb;
   }
   const int nsub = nblk * SPB;
   const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
   float *lrow = nullptr;
-  if (DENSE && p.lws) lrow = p.lws + ((((int64_t)b * p.n_heads + hslot) * p.nqb + i) * nkb) * B + tq;
+  if (SCORES) lrow = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb) * B + tq;
 
-  auto block_of = [&](int e, bool &valid) -> int {
-    if (DENSE) {
-      valid = true;
-      return e;
-    }
+  // key block of sub-tile t (t clamped to the sequence; list entries clamped into [0, row]: memory-safe
+  // whatever the list holds)
+  auto block_of = [&](int t) -> int {
+    int e = (t < nsub ? t : nsub - 1) / SPB;
+    if (DENSE) return e;
     const int j = list[e];
-    valid = (j >= 0) && (j <= i);
-    return valid ? j : 0;
+    return j < 0 ? 0 : (j > row ? row : j);
   };
-  auto issue = [&](int it, int sel) {
-    bool valid;
-    const int j = block_of(it / SPB, valid);
-    const char *src = kvbase + (int64_t)(j * SPB + it % SPB) * STAGE + lane * 16;
-    char *dst = smem + sel * STAGE;
+  // what this wavefront has to do for sub-tile `sub` of key block j: 0 all of it, 1 causal mask, 2 nothing
+  auto mode_of = [&](int j, int sub) -> int {
+    if (!active || j > ib) return 2;
+    if (j != ib) return 0;
+    const int klo = KT * sub, qlo = 32 * wg;
+    return (klo > qlo + 31) ? 2 : ((klo + KT - 1 <= qlo) ? 0 : 1);
+  };
+  // every wavefront moves CH chunks of the image of sub-tile t (clamped) into ring slot `slot_base`
+  auto img_src = [&](int t, int j, bool is_v) -> const char * {
+    const int tt = t < nsub ? t : nsub - 1;
+    return kvbase + (int64_t)(j * SPB + tt % SPB) * STAGE + (is_v ? IMG : 0) + (w * CH) * 1024;
+  };
+  // chunk n (0 .. CH-1) of this wavefront's share of an image
+  auto issue_chunk = [&](const char *src, uint32_t slot_base, int n) {
+    lds_dma16(src + n * 1024, lane * 16, slot_base + (w * CH + n) * 1024);
+  };
+  auto issue_img = [&](int t, int j, bool is_v, uint32_t slot_base) {
+    const char *src = img_src(t, j, is_v);
 #pragma unroll
-    for (int n = 0; n < STAGE / 1024 / NW; ++n) {
-      const int ch = w + n * NW;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + ch * 1024),
-                                       (__attribute__((address_space(3))) void *)(dst + ch * 1024), 16, 0, 0);
-    }
+    for (int n = 0; n < CH; ++n) issue_chunk(src, slot_base, n);
   };
 
-  if (nsub > 0) issue(0, 0);
-  for (int it = 0; it < nsub; ++it) {
-    __builtin_amdgcn_s_waitcnt(0);  // own LDS-direct loads have landed
-    __syncthreads();                // everyone's have; previous tile's readers are done
-    if (it + 1 < nsub) issue(it + 1, (it + 1) & 1);
-
-    const int sub = it % SPB;
-    bool valid;
-    const int j = block_of(it / SPB, valid);
-    int mode = valid ? 0 : 2;  // 0 = no mask, 1 = causal mask inside the tile, 2 = nothing to do
-    if (valid && j == i) {
-      const int klo = KT * sub, qlo = 32 * w;
-      mode = (klo > qlo + 31) ? 2 : ((klo + KT - 1 <= qlo) ? 0 : 1);
-    }
-    if (mode != 2) {
-      const char *kb = smem + (it & 1) * STAGE + lane * 16;
-      const char *vb = kb + IMG;
-      f32x16 s[2];
+  auto qk = [&](const char *kbuf, f32x16(&s)[2]) {
+    const char *kb = kbuf + lane * 16;
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
+      for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
 #pragma unroll
-      for (int ds = 0; ds < DS; ++ds) {
+    for (int ds = 0; ds < DS; ++ds)
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kb + (rb * DS + ds) * 1024);
-          s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ds], s[rb], 0, 0, 0);
-        }
+      for (int rb = 0; rb < 2; ++rb) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kb + (rb * DS + ds) * 1024);
+        s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ds], s[rb], 0, 0, 0);
       }
-      if (mode == 1) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kk = KT * sub + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-            if (kk > tq) s[rb][r] = -INFINITY;
-          }
-      }
-      float mx = s[0][0];
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[rb][r]);
-      mx = fmaxf(mx, xor32(mx));
-      const float m_new = fmaxf(m, mx * p.c);
-      const float alpha = fast_exp2(m - m_new);
-      float rs = 0.f;
+  };
+  // Online softmax, split in two halves that sit in different pipeline steps.
+  // tile_max: (optionally causal-masked) row max of a freshly computed S tile; moves the running max,
+  // rescales the running sums, returns alpha = 2^(m_old - m_new) for the O accumulators.
+  auto tile_max = [&](f32x16(&s)[2], int mode, int sub) -> float {
+    if (mode == 1) {
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float pv = fast_exp2(__builtin_fmaf(s[rb][r], p.c, -m_new));
-          s[rb][r] = pv;
-          rs += pv;
+          const int kk = KT * sub + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (kk > tq) s[rb][r] = -INFINITY;
         }
-      rs += xor32(rs);
-      l = l * alpha + rs;
-      bs = bs * alpha + rs;
-      m = m_new;
-      if (__any(alpha != 1.f)) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-      }
-      bf16x8 pb[4];
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        u32x4 t;
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2)
-          t[e2] = pack_bf16(s[ks >> 1][8 * (ks & 1) + 2 * e2], s[ks >> 1][8 * (ks & 1) + 2 * e2 + 1]);
-        pb[ks] = __builtin_bit_cast(bf16x8, t);
-      }
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vb + (db * 4 + ks) * 1024);
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks], oacc[db], 0, 0, 0);
-        }
-      }
     }
-    if (DENSE && sub == SPB - 1) {
-      // end of key block j: record log2 of the block's exp-sum for this lane's query
-      if (lrow && h == 0) lrow[(int64_t)j * B] = m + fast_log2(bs);
+    float mx = fmaxf(s[0][0], s[0][1]);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int r = (rb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[rb][r], s[rb][r + 1]));
+    mx = max_xor32(mx);
+    const float m_new = fmaxf(m, mx * p.c);
+    const float alpha = fast_exp2(m - m_new);
+    m = m_new;
+    l *= alpha;
+    bs *= alpha;
+    return alpha;
+  };
+  // tile_exp: P = 2^(S*c - m) for a tile whose max is already folded into m; adds the row sums,
+  // leaves P rounded to bf16 in pb (the B operand of the PV product)
+  auto tile_exp = [&](f32x16(&s)[2], bf16x8(&pb)[4]) {
+    float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4 t;
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const int r = 8 * (ks & 1) + 2 * e2;
+#ifdef DIAG_NO_SOFTMAX
+        const float p0 = s[ks >> 1][r], p1 = s[ks >> 1][r + 1];
+#else
+        const float p0 = fast_exp2(__builtin_fmaf(s[ks >> 1][r], p.c, -m));
+        const float p1 = fast_exp2(__builtin_fmaf(s[ks >> 1][r + 1], p.c, -m));
+#endif
+        rs0 += p0;
+        rs1 += p1;
+        t[e2] = pack_bf16(p0, p1);
+      }
+      pb[ks] = __builtin_bit_cast(bf16x8, t);
+    }
+    const float rs = sum_xor32(rs0 + rs1);
+    l += rs;
+    bs += rs;
+  };
+  auto rescale = [&](float alpha) {
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
+  };
+  auto pv = [&](const char *vbuf, const bf16x8(&pb)[4]) {
+    const char *vb = vbuf + lane * 16;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vb + (db * 4 + ks) * 1024);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks], oacc[db], 0, 0, 0);
+      }
+  };
+
+  // On entry to step t: s_cur = raw S[t] (masked where needed), m / l / bs / O already moved to the
+  // running max that includes tile t.  jv = key block of the V image to fetch (tile t+DV), jk = of
+  // the K image (tile t+DK).
+  // sync_and_fill: wait until the images this step reads have landed for every wavefront, then
+  // refill the ring slots the previous step freed.
+#ifdef DIAG_TIMING
+  unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
+  unsigned long long tmark = 0;
+#define TMARK(k) do { const unsigned long long now_ = __builtin_readcyclecounter(); tacc[k] += now_ - tmark; tmark = now_; } while (0)
+#else
+#define TMARK(k) do { } while (0)
+#endif
+  auto sync_and_fill = [&](int t, int jv, int jk, bool fill = true) {
+    TMARK(5);
+    wait_vm<VM_KEEP>();
+    TMARK(0);
+#ifndef DIAG_NO_BARRIER
+    __builtin_amdgcn_s_barrier();
+#endif
+    asm volatile("" ::: "memory");
+    TMARK(1);
+#ifndef DIAG_NO_LOAD
+    if (fill) {
+      issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
+      issue_img(t + DK, jk, false, lds_k + ((t + DK) % RK) * IMG);
+    }
+#endif
+    TMARK(2);
+  };
+  // fast step: tiles t and t+1 both off the diagonal (for every wave group).  One basic block up to
+  // the rescale test.
+  auto fast_step = [&](int t, int j0, int jv, int jk, f32x16(&s_cur)[2], f32x16(&s_next)[2]) {
+#ifdef SP_SPREAD_LOADS
+    sync_and_fill(t, jv, jk, false);
+    const char *src_v = img_src(t + DV, jv, true), *src_k = img_src(t + DK, jk, false);
+    const uint32_t dst_v = lds_v + ((t + DV) % RV) * IMG, dst_k = lds_k + ((t + DK) % RK) * IMG;
+    if (!active) {
+#pragma unroll
+      for (int n = 0; n < CH; ++n) issue_chunk(src_v, dst_v, n);
+#pragma unroll
+      for (int n = 0; n < CH; ++n) issue_chunk(src_k, dst_k, n);
+      return;
+    }
+#else
+    sync_and_fill(t, jv, jk);
+    if (!active) return;
+#endif
+    const char *kb = smem + ((t + 1) % RK) * IMG + lane * 16;
+    const char *vb = smem + (RK + t % RV) * IMG + lane * 16;
+    // Hand-laid schedule: NM groups, each = one MFMA + one LDS read (PF fragments ahead) + a slice
+    // of the VALU work; nothing may cross a group boundary (sched_barrier).
+    //   groups 0 .. NQ-1   : S[t+1] += K frag * Q frag ; exp / row-sum / bf16 pack of S[t]
+    //   groups NQ .. NM-1  : O += V frag * P frag       ; row max of S[t+1], running-max update
+    constexpr int NQ = 2 * DS, NP = 4 * DB, NM = NQ + NP, PF = SGB_PRE;
+    auto frag = [&](int n) -> bf16x8 {
+#ifdef DIAG_NO_LDSREAD
+      return qf[n % DS];
+#endif
+      if (n < NQ) return *reinterpret_cast<const bf16x8 *>(kb + ((n % 2) * DS + n / 2) * 1024);
+      const int np = n - NQ;
+      return *reinterpret_cast<const bf16x8 *>(vb + ((np % DB) * 4 + np / DB) * 1024);
+    };
+    bf16x8 fr[PF + 1];
+    bf16x8 pb[4];
+    u32x4 pt;
+    float rs0 = 0.f, rs1 = 0.f, mx = 0.f, lval = 0.f, alpha = 1.f;
+#pragma unroll
+    for (int n = 0; n < PF; ++n) fr[n] = frag(n);
+#pragma unroll
+    for (int n = 0; n < NM; ++n) {
+#ifdef SP_SPREAD_LOADS
+      // the step's 2*CH LDS-direct loads, one every NM / (2*CH) groups (V image first, then K)
+      if (n % (NM / (2 * CH)) == 0) {
+        const int q_ = n / (NM / (2 * CH));
+        if (q_ < CH) issue_chunk(src_v, dst_v, q_);
+        else if (q_ < 2 * CH) issue_chunk(src_k, dst_k, q_ - CH);
+      }
+#endif
+      if (n + PF < NM) fr[(n + PF) % (PF + 1)] = frag(n + PF);
+      if (n < NQ) {
+        if (n < 2) {
+          f32x16 z;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) z[r] = 0.f;
+          s_next[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], qf[0], z, 0, 0, 0);
+        } else {
+          s_next[n % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], qf[n / 2], s_next[n % 2], 0, 0, 0);
+        }
+        // exp units u (2 scores each) that belong to this group
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          if (u * NQ / 16 != n) continue;
+          const int ks = u / 4, e2 = u % 4, r = 8 * (ks & 1) + 2 * e2;
+#ifdef DIAG_NO_SOFTMAX
+          const float p0 = s_cur[ks >> 1][r], p1 = s_cur[ks >> 1][r + 1];
+#else
+          const float p0 = fast_exp2(__builtin_fmaf(s_cur[ks >> 1][r], p.c, -m));
+          const float p1 = fast_exp2(__builtin_fmaf(s_cur[ks >> 1][r + 1], p.c, -m));
+#endif
+          rs0 += p0;
+          rs1 += p1;
+          pt[e2] = pack_bf16(p0, p1);
+          if (e2 == 3) pb[ks] = __builtin_bit_cast(bf16x8, pt);
+        }
+        if (n == NQ - 1) {
+          const float rs = sum_xor32(rs0 + rs1);
+          l += rs;
+          bs += rs;
+          if (SCORES && t % SPB == SPB - 1) {  // end of key block j0: log2 of the block's exp-sum
+            lval = m + fast_log2(bs);
+            bs = 0.f;
+          }
+        }
+      } else {
+        const int np = n - NQ;
+        oacc[np % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], pb[np / DB], oacc[np % DB], 0, 0, 0);
+        // row max of S[t+1]: 16 max3 units spread over groups 2 .. NP-2, final update in the last group
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          if (2 + u * (NP - 3) / 16 != np) continue;
+          const float a0 = s_next[u / 8][2 * (u % 8)], a1 = s_next[u / 8][2 * (u % 8) + 1];
+          mx = (u == 0) ? fmaxf(a0, a1) : fmaxf(mx, fmaxf(a0, a1));
+        }
+        if (np == NP - 1) {
+          mx = max_xor32(mx);
+          const float m_new = fmaxf(m, mx * p.c);
+          alpha = fast_exp2(m - m_new);
+          m = m_new;
+          l *= alpha;
+          bs *= alpha;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    TMARK(3);
+    rescale(alpha);
+    if (SCORES && t % SPB == SPB - 1 && h == 0) lrow[(int64_t)j0 * B] = lval;
+    TMARK(4);
+  };
+  // general step: per-wavefront causal mask / skip near the diagonal, optional next tile
+  auto slow_step = [&](int t, int j0, int j1, int jv, int jk, f32x16(&s_cur)[2], f32x16(&s_next)[2]) {
+    sync_and_fill(t, jv, jk);
+    const char *k_next = smem + ((t + 1) % RK) * IMG;
+    const char *v_cur = smem + (RK + t % RV) * IMG;
+    const int sub = t % SPB, sub1 = (t + 1) % SPB;
+    const int mode0 = mode_of(j0, sub);
+    const int mode1 = (t + 1 < nsub) ? mode_of(j1, sub1) : 2;
+    if (mode1 != 2) qk(k_next, s_next);
+    if (mode0 != 2) {
+      bf16x8 pb[4];
+      tile_exp(s_cur, pb);
+      pv(v_cur, pb);
+    }
+    if (SCORES && sub == SPB - 1 && mode_of(j0, 0) != 2) {
+      if (h == 0) lrow[(int64_t)j0 * B] = m + fast_log2(bs);
       bs = 0.f;
     }
+    if (mode1 != 2) rescale(tile_max(s_next, mode1, sub1));
+  };
+
+  if (nsub > 0) {
+    // leading run of sub-tiles that lie before the first diagonal entry (of any wave group)
+    int nfast;
+    if (DENSE) {
+      nfast = ((NG == 2) ? 2 * row : row) * SPB;
+    } else {
+      int first = nblk;
+      for (int e = lane; e < nblk; e += 64)
+        if (list[e] >= row) first = first < e ? first : e;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const int o2 = __shfl_xor(first, off, 64);
+        first = first < o2 ? first : o2;
+      }
+      nfast = __builtin_amdgcn_readfirstlane(first) * SPB;
+    }
+    // fast steps need tile t+1 off the diagonal too; keep their count even (tail starts on even parity)
+    nfast = nfast > 0 ? ((nfast - 1) & ~1) : 0;
+
+    f32x16 s_a[2], s_b[2];
+    // jw[n] = key block of sub-tile t + n
+    int jw[6];
+#pragma unroll
+    for (int n = 0; n < 6; ++n) jw[n] = block_of(n);
+    // prologue: K[0 .. DK-1], V[0 .. DV-1]
+#pragma unroll
+    for (int n = 0; n < DK; ++n) {
+      if (n < DV && n < nsub) issue_img(n, jw[n], true, lds_v + (n % RV) * IMG);
+      if (n < nsub) issue_img(n, jw[n], false, lds_k + (n % RK) * IMG);
+    }
+    wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    {
+      const int mode = mode_of(jw[0], 0);
+      if (mode != 2) {
+        qk(smem, s_a);
+        tile_max(s_a, mode, 0);  // O is still zero: nothing to rescale
+      }
+    }
+    int t = 0;
+    for (; t < nfast; t += 2) {
+      const int jn0 = block_of(t + 6), jn1 = block_of(t + 7);
+      fast_step(t, jw[0], jw[DV], jw[DK], s_a, s_b);
+      fast_step(t + 1, jw[1], jw[DV + 1], jw[DK + 1], s_b, s_a);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) jw[n] = jw[n + 2];
+      jw[4] = jn0;
+      jw[5] = jn1;
+    }
+    for (; t < nsub; t += 2) {
+      const int jn0 = block_of(t + 6), jn1 = block_of(t + 7);
+      slow_step(t, jw[0], jw[1], jw[DV], jw[DK], s_a, s_b);
+      if (t + 1 < nsub) slow_step(t + 1, jw[1], jw[2], jw[DV + 1], jw[DK + 1], s_b, s_a);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) jw[n] = jw[n + 2];
+      jw[4] = jn0;
+      jw[5] = jn1;
+    }
+    wait_vm<0>();  // drain the ring's look-ahead loads before the LDS is reused or released
+#ifdef DIAG_TIMING
+    if (lane == 0 && p.dbg) {
+      unsigned long long *d = p.dbg + ((size_t)blockIdx.x * NWT + w) * 8;
+      for (int k = 0; k < 6; ++k) d[k] = tacc[k];
+      d[6] = nsub;
+      d[7] = nfast;
+    }
+#endif
   }
 
   // ---- output: O = O^T accumulators / l, rounded to bf16 ----
-  const float inv = (l > 0.f) ? 1.f / l : 0.f;
-  uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)i * B + tq) * p.o_st + (int64_t)head * p.o_sh;
+  if (active) {
+    const float inv = (l > 0.f) ? 1.f / l : 0.f;
+    uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)ib * B + tq) * p.o_st + (int64_t)head * p.o_sh;
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      u32x2 t;
-      t[0] = pack_bf16(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv);
-      t[1] = pack_bf16(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
-      *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * g + 4 * h) = t;
-    }
+      for (int gq = 0; gq < 4; ++gq) {
+        u32x2 t;
+        t[0] = pack_bf16(oacc[db][4 * gq] * inv, oacc[db][4 * gq + 1] * inv);
+        t[1] = pack_bf16(oacc[db][4 * gq + 2] * inv, oacc[db][4 * gq + 3] * inv);
+        *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * gq + 4 * h) = t;
+      }
+  }
 
-  // ---- block-mass scores: S[i][j] = (1/B) sum_t 2^(lws[j][t] - L_t) ----
-  if (DENSE && p.scores) {
-    if (h == 0) lse_sh[tq] = m + fast_log2(l);
+  // ---- block-mass scores: S[ib][j] = (1/B) sum_t 2^(lws[j][t] - L_t), one row per wave group ----
+  if (SCORES) {
+    float *lse_sh = reinterpret_cast<float *>(smem);  // [NG][B]; the rings are idle now
+    __syncthreads();
+    if (active && h == 0) lse_sh[g * B + tq] = m + fast_log2(l);
     __threadfence();
     __syncthreads();
-    const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hslot) * p.nqb + i) * nkb) * B;
-    float *srow = p.scores + (((int64_t)b * p.n_heads + hslot) * p.nqb + i) * nkb;
-    for (int j = w; j <= i; j += NW) {
-      float acc = 0.f;
+    if (active) {
+      const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb) * B;
+      float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb;
+      for (int j = wg; j <= ib; j += NW) {
+        float acc = 0.f;
 #pragma unroll
-      for (int t = lane; t < B; t += 64) acc += fast_exp2(lblk[(int64_t)j * B + t] - lse_sh[t]);
+        for (int t = lane; t < B; t += 64) acc += fast_exp2(lblk[(int64_t)j * B + t] - lse_sh[g * B + t]);
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-      if (lane == 0) srow[j] = acc * (1.f / B);
+        for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+        if (lane == 0) srow[j] = acc * (1.f / B);
+      }
+      for (int j = ib + 1 + wg * 64 + lane; j < nkb; j += NW * 64) srow[j] = 0.f;
     }
-    for (int j = i + 1 + tid; j < nkb; j += NW * 64) srow[j] = 0.f;
   }
 }
 
@@ -375,8 +707,11 @@ __device__ __forceinline__ uint64_t wave_sum_u64(uint64_t x) {
 }
 
 __device__ __forceinline__ uint32_t quantise24(float s) {
-  if (!(s > 0.f)) return 0u;  // negative, zero and NaN
-  if (s > 1.f) s = 1.f;
+  // bit tests, so the result does not depend on how the compiler treats NaN comparisons
+  const uint32_t bits = __float_as_uint(s);
+  if (bits & 0x80000000u) return 0u;         // negative (and -0, -NaN)
+  if (bits > 0x7F800000u) return 0u;         // NaN
+  if (bits >= 0x3F800000u) return 1u << 24;  // >= 1 (and +inf) clamps to 1
   return (uint32_t)rintf(s * 16777216.f);
 }
 
@@ -609,26 +944,94 @@ void fill_attn(AttnParams &ap, const sp_shape *s, const void *q, const void *kvp
   ap.group = s->n_q_heads / s->n_kv_heads;
   const float scale = (s->softmax_scale > 0.f) ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
   ap.c = scale * 1.4426950408889634f;
+#ifdef DIAG_TIMING
+  ap.dbg = g_dbg_ptr();
+#endif
 }
 
-template <bool DENSE>
-sp_status launch_attn(const sp_shape *s, const AttnParams &ap, hipStream_t st) {
-  const int64_t nwg = (int64_t)s->batch * ap.n_heads * ap.nqb;
+// Host-side view of one attention launch: the listed heads in the caller's order.
+struct HeadList {
+  int n = 0;
+  int32_t head[SP_MAX_HEADS];
+  int32_t map[SP_MAX_HEADS];
+};
+
+// Builds the slot table and launches.  The listed heads are sorted by (kv head, list, head) and
+// dealt to the 8 XCDs in contiguous runs of `ncol` slots, so heads that read the same K/V images
+// (and, for the sparse kernel, walk the same list) run on one XCD together.
+//   dense : one slot per head; with TWO_GROUPS a workgroup takes two consecutive query blocks
+//   sparse: with TWO_GROUPS a slot is a pair of heads with the same (kv head, list); a head left
+//           over runs alone in its slot (second wave group idle)
+template <bool DENSE, int NG>
+sp_status launch_attn_ng(const sp_shape *s, AttnParams ap, const HeadList &hl, hipStream_t st) {
+  const int n = hl.n;
+  struct Ent {
+    int kvh, map, head, pos;
+  } ent[SP_MAX_HEADS];
+  for (int a = 0; a < n; ++a) ent[a] = {hl.head[a] / ap.group, DENSE ? 0 : hl.map[a], hl.head[a], a};
+  std::sort(ent, ent + n, [](const Ent &x, const Ent &y) {
+    if (x.kvh != y.kvh) return x.kvh < y.kvh;
+    if (x.map != y.map) return x.map < y.map;
+    return x.head < y.head;
+  });
+  struct Slot {
+    int a, b, map, pos;
+  } slots[SP_MAX_HEADS];
+  int ns = 0;
+  for (int a = 0; a < n;) {
+    if (!DENSE && NG == 2 && a + 1 < n && ent[a + 1].kvh == ent[a].kvh && ent[a + 1].map == ent[a].map) {
+      slots[ns++] = {ent[a].head, ent[a + 1].head, ent[a].map, ent[a].pos};
+      a += 2;
+    } else {
+      slots[ns++] = {ent[a].head, -1, ent[a].map, ent[a].pos};
+      a += 1;
+    }
+  }
+  ap.n_heads = n;
+  ap.ncol = (ns + 7) / 8;
+  ap.nrows = (DENSE && NG == 2) ? (ap.nqb + 1) / 2 : ap.nqb;
+  for (int a = 0; a < 8 * ap.ncol; ++a) {
+    ap.head_a[a] = a < ns ? slots[a].a : -1;
+    ap.head_b[a] = a < ns ? slots[a].b : -1;
+    ap.head_map[a] = a < ns ? slots[a].map : 0;
+    ap.pos_a[a] = a < ns ? slots[a].pos : 0;
+  }
+  const int64_t nwg = (int64_t)s->batch * 8 * ap.ncol * ap.nrows;
   if (nwg <= 0 || nwg > 0x7FFFFFFF) {
     set_err("grid too large");
     return SP_ERR_UNSUPPORTED;
   }
   dim3 grid((unsigned)nwg);
+  const bool sc = DENSE && ap.scores != nullptr;
   ProfScope prof(DENSE ? KK_DENSE : KK_SPARSE, st);
+#define SP_LAUNCH(D_, B_)                                                                                   \
+  do {                                                                                                      \
+    if (sc)                                                                                                 \
+      hipLaunchKernelGGL((attn_kernel<D_, B_, NG, true, true>), grid, dim3(B_ * 2 * NG), 0, st, ap);       \
+    else                                                                                                    \
+      hipLaunchKernelGGL((attn_kernel<D_, B_, NG, DENSE, false>), grid, dim3(B_ * 2 * NG), 0, st, ap);     \
+  } while (0)
   if (s->head_dim == 128 && s->block == 128)
-    hipLaunchKernelGGL((attn_kernel<128, 128, DENSE>), grid, dim3(256), 0, st, ap);
+    SP_LAUNCH(128, 128);
   else if (s->head_dim == 128 && s->block == 64)
-    hipLaunchKernelGGL((attn_kernel<128, 64, DENSE>), grid, dim3(128), 0, st, ap);
+    SP_LAUNCH(128, 64);
   else if (s->head_dim == 64 && s->block == 128)
-    hipLaunchKernelGGL((attn_kernel<64, 128, DENSE>), grid, dim3(256), 0, st, ap);
+    SP_LAUNCH(64, 128);
   else
-    hipLaunchKernelGGL((attn_kernel<64, 64, DENSE>), grid, dim3(128), 0, st, ap);
+    SP_LAUNCH(64, 64);
+#undef SP_LAUNCH
   return hip_check(hipGetLastError(), DENSE ? "dense attn_kernel launch" : "sparse attn_kernel launch");
+}
+
+#ifndef SP_DENSE_NG
+#define SP_DENSE_NG 1
+#endif
+#ifndef SP_SPARSE_NG
+#define SP_SPARSE_NG 1
+#endif
+template <bool DENSE>
+sp_status launch_attn(const sp_shape *s, const AttnParams &ap, const HeadList &hl, hipStream_t st) {
+  return launch_attn_ng<DENSE, DENSE ? SP_DENSE_NG : SP_SPARSE_NG>(s, ap, hl, st);
 }
 
 sp_status launch_mask(const float *scores, int n_maps, int nqb, int nkb, float gamma, int32_t *kb_idx,
@@ -679,6 +1082,10 @@ const char *sp_status_string(sp_status s) {
 }
 
 const char *sp_last_error(void) { return g_err; }
+
+#ifdef DIAG_TIMING
+void sp_debug_set_buffer(void *p) { g_dbg_store = (unsigned long long *)p; }
+#endif
 
 sp_status sp_profile_enable(int32_t on) {
   g_prof_on = on != 0;
@@ -752,11 +1159,12 @@ sp_status sp_dense_attn_with_block_scores(const sp_shape *shape, const void *q, 
   if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
   AttnParams ap;
   fill_attn(ap, shape, q, workspace, o);
-  ap.n_heads = n_heads;
-  for (int a = 0; a < n_heads; ++a) ap.head_ids[a] = head_ids[a];
+  HeadList hl;
+  hl.n = n_heads;
+  for (int a = 0; a < n_heads; ++a) hl.head[a] = head_ids[a];
   ap.lws = block_scores ? (float *)((char *)workspace + pack_bytes(shape)) : nullptr;
   ap.scores = block_scores;
-  return launch_attn<true>(shape, ap, st);
+  return launch_attn<true>(shape, ap, hl, st);
 }
 
 sp_status sp_build_block_mask(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb, float gamma,
@@ -818,15 +1226,16 @@ sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void 
   if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
   AttnParams ap;
   fill_attn(ap, shape, q, workspace, o);
-  ap.n_heads = n_heads;
+  HeadList hl;
+  hl.n = n_heads;
   ap.n_maps = n_maps;
   for (int a = 0; a < n_heads; ++a) {
-    ap.head_ids[a] = head_ids[a];
-    ap.head_map[a] = head_map[a];
+    hl.head[a] = head_ids[a];
+    hl.map[a] = head_map[a];
   }
   ap.kb_idx = kb_idx;
   ap.kb_cnt = kb_cnt;
-  return launch_attn<false>(shape, ap, st);
+  return launch_attn<false>(shape, ap, hl, st);
 }
 
 sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
@@ -879,38 +1288,37 @@ sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, 
   // 1. pivots: dense attention + block-mass scores (Alg. 1 line 8 with M = ones, Alg. 4)
   AttnParams ap;
   fill_attn(ap, shape, q, workspace, o);
-  ap.n_heads = n_clusters;
-  for (int c = 0; c < n_clusters; ++c) ap.head_ids[c] = pivot_heads[c];
+  HeadList hl;
+  hl.n = n_clusters;
+  for (int c = 0; c < n_clusters; ++c) hl.head[c] = pivot_heads[c];
   ap.lws = (float *)((char *)workspace + pack_bytes(shape));
   ap.scores = block_scores;
-  if ((rc = launch_attn<true>(shape, ap, st))) return rc;
+  if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
   // 2. heads outside every cluster: dense, no scores
-  int n_free = 0;
   fill_attn(ap, shape, q, workspace, o);
+  hl.n = 0;
   for (int hq = 0; hq < Hq; ++hq)
-    if (head_to_cluster[hq] < 0) ap.head_ids[n_free++] = hq;
-  if (n_free) {
-    ap.n_heads = n_free;
-    if ((rc = launch_attn<true>(shape, ap, st))) return rc;
+    if (head_to_cluster[hq] < 0) hl.head[hl.n++] = hq;
+  if (hl.n) {
+    if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
   }
   // 3. one pattern per (batch, cluster) (Alg. 2)
   if ((rc = launch_mask(block_scores, shape->batch * n_clusters, nqb, nqb, gamma, kb_idx, kb_cnt, nullptr, st)))
     return rc;
   // 4. remaining heads share their cluster's pattern (Alg. 4) and run block-sparse (Sec. 5.1)
-  int n_sparse = 0;
   fill_attn(ap, shape, q, workspace, o);
+  hl.n = 0;
   for (int hq = 0; hq < Hq; ++hq)
     if (head_to_cluster[hq] >= 0 && !is_pivot[hq]) {
-      ap.head_ids[n_sparse] = hq;
-      ap.head_map[n_sparse] = head_to_cluster[hq];
-      ++n_sparse;
+      hl.head[hl.n] = hq;
+      hl.map[hl.n] = head_to_cluster[hq];
+      ++hl.n;
     }
-  if (n_sparse) {
-    ap.n_heads = n_sparse;
+  if (hl.n) {
     ap.n_maps = n_clusters;
     ap.kb_idx = kb_idx;
     ap.kb_cnt = kb_cnt;
-    if ((rc = launch_attn<false>(shape, ap, st))) return rc;
+    if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
   }
   return SP_OK;
 }
