@@ -28,6 +28,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
+# HBM/fabric bytes per launch of the dense-pivot kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# passes summarised in profiles/prefill_layer_llama8b_128k.md (counters scaled by a 1 GiB copy; a
+# benchmark run cannot collect counters itself, so the figure is carried here per workload)
+MEASURED_TRAFFIC_BYTES = {"llama8b_128k": 18.97e9}
 
 
 def main() -> int:
@@ -154,7 +158,10 @@ def main() -> int:
         "speedup_vs_dense": (dense_all_ms / ms_step) if dense_all_ms else None,
         "roofline": {"kernel": "attn_kernel<dense> (pivot heads + block scores)", "bound": "mfma",
                      "achieved": dense_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": dense_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": dense_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.seq is None else None,
+                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
+                     "algorithmic_flops_per_launch": dense_flops_per_launch,
                      "launch_ms": dense_avg_ms},
         "input_gen_s": gen_s,
     }

@@ -113,9 +113,10 @@ sp_status sp_build_block_mask(const float *block_scores, int32_t n_maps, int32_t
  *   head_ids host [n_heads] distinct query heads; head_map host [n_heads] in [0,n_maps)
  *   kb_idx   device int32 [batch][n_maps][nqb][nkb]; kb_cnt device int32 [batch][n_maps][nqb]
  *   o        device bf16; only the listed heads' rows are written
- * Entries of a list that are out of range or above the diagonal are skipped; a
- * query block whose list is empty gets zeros.  The packed K/V copy lives in
- * `workspace`.
+ * Lists must be ascending, without repeats, every entry in [0, i]; the kernel clamps
+ * entries into [0, i] (so the call stays memory-safe whatever the buffer holds, but
+ * the output of a row whose list breaks the rule is unspecified).  A query block
+ * whose count is 0 gets zeros.  The packed K/V copy lives in `workspace`.
  */
 sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void *k, const void *v,
                                const int32_t *head_ids, const int32_t *head_map, int32_t n_heads,

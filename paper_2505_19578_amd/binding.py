@@ -44,6 +44,9 @@ def lib() -> ctypes.CDLL:
     """Load libshareprefill.so (built on demand if absent); raises if that fails."""
     global _lib
     if _lib is None:
+        # torch first: its bundled HIP runtime owns the device memory the calls receive, and the
+        # library must bind to that same runtime instance rather than load a second copy
+        import torch  # noqa: F401
         L = ctypes.CDLL(library_path())
         vp, ip, fp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p
         sp = ctypes.POINTER(SpShape)

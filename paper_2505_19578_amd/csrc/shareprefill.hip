@@ -24,6 +24,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <utility>
 #include <cmath>
 #include <cstdarg>
 #include <cstdint>
@@ -153,10 +154,16 @@ constexpr int SP_MAX_SLOTS = SP_MAX_HEADS + 8;
 #define SGB_N 1
 #endif
 #ifndef SP_DK1
-#define SP_DK1 3
+#define SP_DK1 2
 #endif
 #ifndef SP_DV1
 #define SP_DV1 1
+#endif
+#ifndef SP_MAXTAIL
+#define SP_MAXTAIL 4
+#endif
+#ifndef SP_PRIO
+#define SP_PRIO 0
 #endif
 #ifndef SGB_PRE
 #define SGB_PRE 4
@@ -200,6 +207,17 @@ __device__ __forceinline__ float sum_xor32(float x) {
   const uint32_t u = __builtin_bit_cast(uint32_t, x);
   const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+
+// compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1, so that every index derived
+// from I is a constant expression (register arrays never get a run-time subscript)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -497,6 +515,7 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
     float rs0 = 0.f, rs1 = 0.f, mx = 0.f, lval = 0.f, alpha = 1.f;
 #pragma unroll
     for (int n = 0; n < PF; ++n) fr[n] = frag(n);
+    if (SP_PRIO) __builtin_amdgcn_s_setprio(SP_PRIO);
 #pragma unroll
     for (int n = 0; n < NM; ++n) {
 #ifdef SP_SPREAD_LOADS
@@ -545,14 +564,15 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
       } else {
         const int np = n - NQ;
         oacc[np % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], pb[np / DB], oacc[np % DB], 0, 0, 0);
-        // row max of S[t+1]: 16 max3 units spread over groups 2 .. NP-2, final update in the last group
+        // row max of S[t+1]: 16 max3 units spread over groups 2 .. NP-1-SP_MAXTAIL, then the running-max
+        // update SP_MAXTAIL groups before the end (its dependent chain hides under the last MFMAs)
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
-          if (2 + u * (NP - 3) / 16 != np) continue;
+          if (2 + u * (NP - 2 - SP_MAXTAIL) / 16 != np) continue;
           const float a0 = s_next[u / 8][2 * (u % 8)], a1 = s_next[u / 8][2 * (u % 8) + 1];
           mx = (u == 0) ? fmaxf(a0, a1) : fmaxf(mx, fmaxf(a0, a1));
         }
-        if (np == NP - 1) {
+        if (np == NP - SP_MAXTAIL) {
           mx = max_xor32(mx);
           const float m_new = fmaxf(m, mx * p.c);
           alpha = fast_exp2(m - m_new);
@@ -563,6 +583,7 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (SP_PRIO) __builtin_amdgcn_s_setprio(0);
     TMARK(3);
     rescale(alpha);
     if (SCORES && t % SPB == SPB - 1 && h == 0) lrow[(int64_t)j0 * B] = lval;
@@ -693,6 +714,426 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
         if (lane == 0) srow[j] = acc * (1.f / B);
       }
       for (int j = ib + 1 + wg * 64 + lane; j < nkb; j += NW * 64) srow[j] = 0.f;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// attention kernel, wide variant (block = 128): 64 queries per wavefront, one wavefront per SIMD
+// ---------------------------------------------------------------------------------------------
+// Same pipeline as attn_kernel, but every wavefront owns two 32-query halves, so each K / V
+// fragment read from LDS and each byte brought through the vector L1 feeds two MFMAs.  A workgroup
+// is 4 wavefronts = 256 queries = two wave groups (two consecutive query blocks of one head, or one
+// query block of two heads that use the same list), one workgroup per CU, 4-deep K and V rings
+// (128 KiB of LDS at head_dim 128).  With half as many LDS / VMEM instructions per MFMA a single
+// wavefront keeps the matrix pipe busy on its own, which is what the 512-register budget buys.
+template <int D, bool DENSE, bool SCORES>
+__global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
+  constexpr int B = 128;
+  constexpr int NWT = 4;            // wavefronts per workgroup, 64 queries each
+  constexpr int SPB = B / KT;       // sub-tiles per key block
+  constexpr int IMG = KT * D * 2;   // bytes of a packed K (or V) image
+  constexpr int STAGE = 2 * IMG;
+  constexpr int DS = D / 16;
+  constexpr int DB = D / 32;
+  constexpr int DK = 4, DV = 3;
+  constexpr int RK = DK, RV = DV + 1;
+  constexpr int CH = IMG / 1024 / NWT;
+  constexpr int VM_KEEP = ((2 * DV - 1) < (2 * DK - 4) ? (2 * DV - 1) : (2 * DK - 4)) * CH;
+  __shared__ __attribute__((aligned(1024))) char smem[(RK + RV) * IMG];
+  const uint32_t lds_k = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
+  const uint32_t lds_v = lds_k + RK * IMG;
+
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, c32 = lane & 31;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = w >> 1, wg = w & 1;  // wave group, wavefront inside the group (64 queries each)
+  const int xcd = blockIdx.x & 7;
+  int rest = blockIdx.x >> 3;
+  const int slot = xcd * p.ncol + rest % p.ncol;
+  rest /= p.ncol;
+  const int row = p.nrows - 1 - (rest % p.nrows);
+  const int b = rest / p.nrows;
+  if (p.head_a[slot] < 0) return;
+  const int nkb = p.nqb;
+  const int head = (!DENSE && g == 1) ? p.head_b[slot] : p.head_a[slot];
+  const int ib = DENSE ? 2 * row + g : row;
+  const bool active = head >= 0 && ib < p.nqb;
+  const int hpos = p.pos_a[slot];
+  const int kvh = p.head_a[slot] / p.group;
+
+  int tq[2];  // this lane's two queries inside the block
+  tq[0] = 64 * wg + c32;
+  tq[1] = tq[0] + 32;
+  bf16x8 qf[2][DS];
+#pragma unroll
+  for (int qh = 0; qh < 2; ++qh) {
+    if (active) {
+      const uint16_t *qp =
+          p.q + (int64_t)b * p.q_sb + ((int64_t)ib * B + tq[qh]) * p.q_st + (int64_t)head * p.q_sh + 8 * h;
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds) qf[qh][ds] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
+    } else {
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[qh][ds][e] = (__bf16)0.f;
+    }
+  }
+  f32x16 oacc[2][DB];
+#pragma unroll
+  for (int qh = 0; qh < 2; ++qh)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[qh][db][r] = 0.f;
+  float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f}, bs[2] = {0.f, 0.f};
+
+  int nblk;
+  const int32_t *list = nullptr;
+  if (DENSE) {
+    nblk = (2 * row + 1 < p.nqb) ? 2 * row + 2 : 2 * row + 1;
+  } else {
+    const int64_t lrow_id = ((int64_t)b * p.n_maps + p.head_map[slot]) * p.nqb + row;
+    nblk = p.kb_cnt[lrow_id];
+    nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
+    list = p.kb_idx + lrow_id * nkb;
+  }
+  const int nsub = nblk * SPB;
+  const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
+  float *lrow = nullptr;  // block-local log-sum-exp row of query tq[0]; tq[1] sits 32 floats further
+  if (SCORES) lrow = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb) * B + tq[0];
+
+  auto block_of = [&](int t) -> int {
+    int e = (t < nsub ? t : nsub - 1) / SPB;
+    if (DENSE) return e;
+    const int j = list[e];
+    return j < 0 ? 0 : (j > row ? row : j);
+  };
+  // what half qh of this wavefront has to do for sub-tile `sub` of key block j:
+  // 0 all of it, 1 causal mask, 2 nothing
+  auto mode_of = [&](int j, int sub, int qh) -> int {
+    if (!active || j > ib) return 2;
+    if (j != ib) return 0;
+    const int klo = KT * sub, qlo = 64 * wg + 32 * qh;
+    return (klo > qlo + 31) ? 2 : ((klo + KT - 1 <= qlo) ? 0 : 1);
+  };
+  auto img_src = [&](int t, int j, bool is_v) -> const char * {
+    const int tt = t < nsub ? t : nsub - 1;
+    return kvbase + (int64_t)(j * SPB + tt % SPB) * STAGE + (is_v ? IMG : 0) + (w * CH) * 1024;
+  };
+  auto issue_img = [&](int t, int j, bool is_v, uint32_t slot_base) {
+    const char *src = img_src(t, j, is_v);
+#pragma unroll
+    for (int n = 0; n < CH; ++n) lds_dma16(src + n * 1024, lane * 16, slot_base + (w * CH + n) * 1024);
+  };
+  auto sync_and_fill = [&](int t, int jv, int jk) {
+    wait_vm<VM_KEEP>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
+    issue_img(t + DK, jk, false, lds_k + ((t + DK) % RK) * IMG);
+  };
+
+  // ---- building blocks of the general (near-diagonal) step, one 32-query half at a time ----
+  auto qk_half = [&](const char *kbuf, int qh, f32x16(&s)[2]) {
+    const char *kb = kbuf + lane * 16;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kb + (rb * DS + ds) * 1024);
+        s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qh][ds], s[rb], 0, 0, 0);
+      }
+  };
+  auto max_half = [&](f32x16(&s)[2], int qh, int mode, int sub) -> float {
+    if (mode == 1) {
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kk = KT * sub + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (kk > tq[qh]) s[rb][r] = -INFINITY;
+        }
+    }
+    float mx = fmaxf(s[0][0], s[0][1]);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int r = (rb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[rb][r], s[rb][r + 1]));
+    mx = max_xor32(mx);
+    const float m_new = fmaxf(m[qh], mx * p.c);
+    const float alpha = fast_exp2(m[qh] - m_new);
+    m[qh] = m_new;
+    l[qh] *= alpha;
+    bs[qh] *= alpha;
+    return alpha;
+  };
+  auto exp_half = [&](f32x16(&s)[2], int qh, bf16x8(&pb)[4]) {
+    float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4 t;
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const int r = 8 * (ks & 1) + 2 * e2;
+        const float p0 = fast_exp2(__builtin_fmaf(s[ks >> 1][r], p.c, -m[qh]));
+        const float p1 = fast_exp2(__builtin_fmaf(s[ks >> 1][r + 1], p.c, -m[qh]));
+        rs0 += p0;
+        rs1 += p1;
+        t[e2] = pack_bf16(p0, p1);
+      }
+      pb[ks] = __builtin_bit_cast(bf16x8, t);
+    }
+    const float rs = sum_xor32(rs0 + rs1);
+    l[qh] += rs;
+    bs[qh] += rs;
+  };
+  auto rescale_half = [&](int qh, float alpha) {
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[qh][db][r] *= alpha;
+    }
+  };
+  auto pv_half = [&](const char *vbuf, int qh, const bf16x8(&pb)[4]) {
+    const char *vb = vbuf + lane * 16;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vb + (db * 4 + ks) * 1024);
+        oacc[qh][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks], oacc[qh][db], 0, 0, 0);
+      }
+  };
+
+  // fast step: tiles t and t+1 off the diagonal for every wavefront.  Hand-laid schedule of
+  // NM = NQ + NP groups, one MFMA each; an LDS fragment feeds two consecutive groups (both halves).
+  //   groups 0 .. NQ-1        S[t+1][qh] += K frag * Q frag[qh]
+  //   groups NQ .. NM-1       O[qh] += V frag * P[t][qh] frag
+  //   VALU, spread evenly:    exp / row-sum / bf16 pack of S[t] over groups 0 .. 3NM/4-1 (the PV groups
+  //                           of the first 32 keys only need the first half of P), then the row max
+  //                           of S[t+1] and the running-max update in the last quarter.
+  auto fast_step = [&](int t, int j0, int jv, int jk, f32x16(&s_cur)[2][2], f32x16(&s_next)[2][2]) {
+    sync_and_fill(t, jv, jk);
+    if (!active) return;
+    const char *kb = smem + ((t + 1) % RK) * IMG + lane * 16;
+    const char *vb = smem + (RK + t % RV) * IMG + lane * 16;
+    constexpr int NFQ = 2 * DS, NFP = 4 * DB, NF = NFQ + NFP;  // fragments: K then V
+    constexpr int NQ = 2 * NFQ, NM = 2 * NF, PF = SGB_PRE;      // groups
+    constexpr int NEXP = (3 * NM) / 4;                            // groups that carry exp units
+    auto frag = [&](int f) -> bf16x8 {
+      if (f < NFQ) return *reinterpret_cast<const bf16x8 *>(kb + ((f % 2) * DS + f / 2) * 1024);
+      const int fp = f - NFQ;
+      return *reinterpret_cast<const bf16x8 *>(vb + ((fp % DB) * 4 + fp / DB) * 1024);
+    };
+    bf16x8 fr[PF + 1];
+    bf16x8 pb[2][4];
+    u32x4 pt;
+    float rs0[2] = {0.f, 0.f}, rs1[2] = {0.f, 0.f}, mx[2] = {0.f, 0.f}, lval[2] = {0.f, 0.f};
+    float alpha[2] = {1.f, 1.f};
+#pragma unroll
+    for (int f = 0; f < PF; ++f) fr[f] = frag(f);
+    static_for<NM>([&](auto nc) {
+      constexpr int n = decltype(nc)::value;
+      constexpr int f = n / 2, qh = n % 2;
+      if constexpr (qh == 0 && f + PF < NF) fr[(f + PF) % (PF + 1)] = frag(f + PF);
+      if constexpr (n < NQ) {
+        constexpr int rb = f % 2, ds = f / 2;
+        if constexpr (f < 2) {
+          f32x16 z;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) z[r] = 0.f;
+          s_next[qh][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % (PF + 1)], qf[qh][ds], z, 0, 0, 0);
+        } else {
+          s_next[qh][rb] =
+              __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % (PF + 1)], qf[qh][ds], s_next[qh][rb], 0, 0, 0);
+        }
+      } else {
+        constexpr int fp = f - NFQ, ks = fp / DB, db = fp % DB;
+        oacc[qh][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % (PF + 1)], pb[qh][ks], oacc[qh][db], 0, 0, 0);
+      }
+      // exp units: u = 8 ks + 4 qh' + e2, two scores each, unit u rides in group u * NEXP / 32
+      constexpr int u_lo = (32 * n + NEXP - 1) / NEXP, u_hi = (32 * (n + 1) + NEXP - 1) / NEXP;
+      static_for<(u_hi < 32 ? u_hi : 32) - (u_lo < 32 ? u_lo : 32)>([&](auto uc) {
+        constexpr int u = u_lo + decltype(uc)::value;
+        constexpr int ks = u / 8, q2 = (u / 4) % 2, e2 = u % 4, r = 8 * (ks & 1) + 2 * e2;
+        const float p0 = fast_exp2(__builtin_fmaf(s_cur[q2][ks >> 1][r], p.c, -m[q2]));
+        const float p1 = fast_exp2(__builtin_fmaf(s_cur[q2][ks >> 1][r + 1], p.c, -m[q2]));
+        rs0[q2] += p0;
+        rs1[q2] += p1;
+        pt[e2] = pack_bf16(p0, p1);
+        if constexpr (e2 == 3) pb[q2][ks] = __builtin_bit_cast(bf16x8, pt);
+      });
+      if constexpr (n == NEXP - 1 || n == NEXP) {  // row sums of the finished P tile, one half per group
+        constexpr int q2 = n - (NEXP - 1);
+        const float rs = sum_xor32(rs0[q2] + rs1[q2]);
+        l[q2] += rs;
+        bs[q2] += rs;
+        if (SCORES && t % SPB == SPB - 1) {  // end of key block j0: log2 of the block's exp-sum
+          lval[q2] = m[q2] + fast_log2(bs[q2]);
+          bs[q2] = 0.f;
+        }
+      }
+      // row max of S[t+1]: 32 units (two scores each) over groups NEXP+1 .. NM-5, then one
+      // running-max update per half in groups NM-4 and NM-3
+      if constexpr (n > NEXP && n < NM - 4) {
+        constexpr int NMX = NM - 5 - NEXP;  // groups that carry max units
+        constexpr int nn = n - (NEXP + 1);
+        constexpr int v_lo = (32 * nn + NMX - 1) / NMX, v_hi = (32 * (nn + 1) + NMX - 1) / NMX;
+        static_for<(v_hi < 32 ? v_hi : 32) - (v_lo < 32 ? v_lo : 32)>([&](auto vc) {
+          constexpr int u = v_lo + decltype(vc)::value;
+          constexpr int q2 = u / 16, rb = (u / 8) % 2, r = 2 * (u % 8);
+          const float a0 = s_next[q2][rb][r], a1 = s_next[q2][rb][r + 1];
+          if constexpr (u % 16 == 0) mx[q2] = fmaxf(a0, a1);
+          else mx[q2] = fmaxf(mx[q2], fmaxf(a0, a1));
+        });
+      }
+      if constexpr (n == NM - 4 || n == NM - 3) {
+        constexpr int q2 = n - (NM - 4);
+        const float mq = max_xor32(mx[q2]);
+        const float m_new = fmaxf(m[q2], mq * p.c);
+        alpha[q2] = fast_exp2(m[q2] - m_new);
+        m[q2] = m_new;
+        l[q2] *= alpha[q2];
+        bs[q2] *= alpha[q2];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    rescale_half(0, alpha[0]);
+    rescale_half(1, alpha[1]);
+    if (SCORES && t % SPB == SPB - 1 && h == 0) {
+      lrow[(int64_t)j0 * B] = lval[0];
+      lrow[(int64_t)j0 * B + 32] = lval[1];
+    }
+  };
+  // general step: per-half causal mask / skip near the diagonal, optional next tile
+  auto slow_step = [&](int t, int j0, int j1, int jv, int jk, f32x16(&s_cur)[2][2], f32x16(&s_next)[2][2]) {
+    sync_and_fill(t, jv, jk);
+    const char *k_next = smem + ((t + 1) % RK) * IMG;
+    const char *v_cur = smem + (RK + t % RV) * IMG;
+    const int sub = t % SPB, sub1 = (t + 1) % SPB;
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh) {
+      const int mode0 = mode_of(j0, sub, qh);
+      const int mode1 = (t + 1 < nsub) ? mode_of(j1, sub1, qh) : 2;
+      if (mode1 != 2) qk_half(k_next, qh, s_next[qh]);
+      if (mode0 != 2) {
+        bf16x8 pb[4];
+        exp_half(s_cur[qh], qh, pb);
+        pv_half(v_cur, qh, pb);
+      }
+      if (SCORES && sub == SPB - 1 && mode_of(j0, 0, qh) != 2) {
+        if (h == 0) lrow[(int64_t)j0 * B + 32 * qh] = m[qh] + fast_log2(bs[qh]);
+        bs[qh] = 0.f;
+      }
+      if (mode1 != 2) rescale_half(qh, max_half(s_next[qh], qh, mode1, sub1));
+    }
+  };
+
+  if (nsub > 0) {
+    int nfast;
+    if (DENSE) {
+      nfast = 2 * row * SPB;
+    } else {
+      int first = nblk;
+      for (int e = lane; e < nblk; e += 64)
+        if (list[e] >= row) first = first < e ? first : e;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const int o2 = __shfl_xor(first, off, 64);
+        first = first < o2 ? first : o2;
+      }
+      nfast = __builtin_amdgcn_readfirstlane(first) * SPB;
+    }
+    nfast = nfast > 0 ? ((nfast - 1) & ~1) : 0;
+
+    f32x16 s_a[2][2], s_b[2][2];
+    int jw[6];
+#pragma unroll
+    for (int n = 0; n < 6; ++n) jw[n] = block_of(n);
+#pragma unroll
+    for (int n = 0; n < DK; ++n) {
+      if (n < DV && n < nsub) issue_img(n, jw[n], true, lds_v + (n % RV) * IMG);
+      if (n < nsub) issue_img(n, jw[n], false, lds_k + (n % RK) * IMG);
+    }
+    wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh) {
+      const int mode = mode_of(jw[0], 0, qh);
+      if (mode != 2) {
+        qk_half(smem, qh, s_a[qh]);
+        max_half(s_a[qh], qh, mode, 0);  // O is still zero: nothing to rescale
+      }
+    }
+    int t = 0;
+    for (; t < nfast; t += 2) {
+      const int jn0 = block_of(t + 6), jn1 = block_of(t + 7);
+      fast_step(t, jw[0], jw[DV], jw[DK], s_a, s_b);
+      fast_step(t + 1, jw[1], jw[DV + 1], jw[DK + 1], s_b, s_a);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) jw[n] = jw[n + 2];
+      jw[4] = jn0;
+      jw[5] = jn1;
+    }
+    for (; t < nsub; t += 2) {
+      const int jn0 = block_of(t + 6), jn1 = block_of(t + 7);
+      slow_step(t, jw[0], jw[1], jw[DV], jw[DK], s_a, s_b);
+      if (t + 1 < nsub) slow_step(t + 1, jw[1], jw[2], jw[DV + 1], jw[DK + 1], s_b, s_a);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) jw[n] = jw[n + 2];
+      jw[4] = jn0;
+      jw[5] = jn1;
+    }
+    wait_vm<0>();  // drain the ring's look-ahead loads before the LDS is reused or released
+  }
+
+  // ---- output: O = O^T accumulators / l, rounded to bf16 ----
+  if (active) {
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh) {
+      const float inv = (l[qh] > 0.f) ? 1.f / l[qh] : 0.f;
+      uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)ib * B + tq[qh]) * p.o_st + (int64_t)head * p.o_sh;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          u32x2 tt;
+          tt[0] = pack_bf16(oacc[qh][db][4 * gq] * inv, oacc[qh][db][4 * gq + 1] * inv);
+          tt[1] = pack_bf16(oacc[qh][db][4 * gq + 2] * inv, oacc[qh][db][4 * gq + 3] * inv);
+          *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * gq + 4 * h) = tt;
+        }
+    }
+  }
+
+  // ---- block-mass scores: S[ib][j] = (1/B) sum_t 2^(lws[j][t] - L_t), one row per wave group ----
+  if (SCORES) {
+    float *lse_sh = reinterpret_cast<float *>(smem);  // [2][B]; the rings are idle now
+    __syncthreads();
+    if (active && h == 0) {
+      lse_sh[g * B + tq[0]] = m[0] + fast_log2(l[0]);
+      lse_sh[g * B + tq[1]] = m[1] + fast_log2(l[1]);
+    }
+    __threadfence();
+    __syncthreads();
+    if (active) {
+      const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb) * B;
+      float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb;
+      for (int j = wg; j <= ib; j += 2) {
+        float acc = 0.f;
+#pragma unroll
+        for (int t = lane; t < B; t += 64) acc += fast_exp2(lblk[(int64_t)j * B + t] - lse_sh[g * B + t]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+        if (lane == 0) srow[j] = acc * (1.f / B);
+      }
+      for (int j = ib + 1 + wg * 64 + lane; j < nkb; j += 2 * 64) srow[j] = 0.f;
     }
   }
 }
@@ -962,7 +1403,7 @@ struct HeadList {
 //   dense : one slot per head; with TWO_GROUPS a workgroup takes two consecutive query blocks
 //   sparse: with TWO_GROUPS a slot is a pair of heads with the same (kv head, list); a head left
 //           over runs alone in its slot (second wave group idle)
-template <bool DENSE, int NG>
+template <bool DENSE, int NG, bool WIDE>
 sp_status launch_attn_ng(const sp_shape *s, AttnParams ap, const HeadList &hl, hipStream_t st) {
   const int n = hl.n;
   struct Ent {
@@ -1011,7 +1452,19 @@ sp_status launch_attn_ng(const sp_shape *s, AttnParams ap, const HeadList &hl, h
     else                                                                                                    \
       hipLaunchKernelGGL((attn_kernel<D_, B_, NG, DENSE, false>), grid, dim3(B_ * 2 * NG), 0, st, ap);     \
   } while (0)
-  if (s->head_dim == 128 && s->block == 128)
+#define SP_LAUNCH_WIDE(D_)                                                                   \
+  do {                                                                                       \
+    if (sc)                                                                                  \
+      hipLaunchKernelGGL((attn_wide_kernel<D_, true, true>), grid, dim3(256), 0, st, ap);   \
+    else                                                                                     \
+      hipLaunchKernelGGL((attn_wide_kernel<D_, DENSE, false>), grid, dim3(256), 0, st, ap); \
+  } while (0)
+  if (WIDE && s->block == 128) {
+    if (s->head_dim == 128)
+      SP_LAUNCH_WIDE(128);
+    else
+      SP_LAUNCH_WIDE(64);
+  } else if (s->head_dim == 128 && s->block == 128)
     SP_LAUNCH(128, 128);
   else if (s->head_dim == 128 && s->block == 64)
     SP_LAUNCH(128, 64);
@@ -1020,18 +1473,23 @@ sp_status launch_attn_ng(const sp_shape *s, AttnParams ap, const HeadList &hl, h
   else
     SP_LAUNCH(64, 64);
 #undef SP_LAUNCH
+#undef SP_LAUNCH_WIDE
   return hip_check(hipGetLastError(), DENSE ? "dense attn_kernel launch" : "sparse attn_kernel launch");
 }
 
-#ifndef SP_DENSE_NG
-#define SP_DENSE_NG 1
+#ifndef SP_DENSE_WIDE
+#define SP_DENSE_WIDE 0
 #endif
-#ifndef SP_SPARSE_NG
-#define SP_SPARSE_NG 1
+#ifndef SP_SPARSE_WIDE
+#define SP_SPARSE_WIDE 0
 #endif
+// block 128: the wide kernel (two wave groups per workgroup, 64 queries per wavefront);
+// block 64: the narrow kernel, one query block per workgroup
 template <bool DENSE>
 sp_status launch_attn(const sp_shape *s, const AttnParams &ap, const HeadList &hl, hipStream_t st) {
-  return launch_attn_ng<DENSE, DENSE ? SP_DENSE_NG : SP_SPARSE_NG>(s, ap, hl, st);
+  constexpr bool kWide = DENSE ? (SP_DENSE_WIDE != 0) : (SP_SPARSE_WIDE != 0);
+  if (kWide && s->block == 128) return launch_attn_ng<DENSE, 2, true>(s, ap, hl, st);
+  return launch_attn_ng<DENSE, 1, false>(s, ap, hl, st);
 }
 
 sp_status launch_mask(const float *scores, int n_maps, int nqb, int nkb, float gamma, int32_t *kb_idx,
