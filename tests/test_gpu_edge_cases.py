@@ -1,0 +1,178 @@
+"""GPU edge cases of the C-ABI calls against the CPU oracle: batch > 1, strided (interleaved QKV) layouts,
+a caller-given softmax scale, caller-made key-block lists (all-ones = dense, sink + diagonal only, empty),
+heads outside every cluster, the bitmask output, every mask-kernel code path (rows in registers / re-read
+rows / nkb not a multiple of 64), special score values, and run-to-run determinism."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+OUT_MAX, OUT_MEAN = 2e-2, 2e-3
+
+
+def _dev(bits):
+    import torch
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def _f32(bits):
+    from synth import bf16_bits_to_f32
+    return bf16_bits_to_f32(bits)
+
+
+def _err(got, want):
+    d = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    return float(d.max()), float(d.mean())
+
+
+def test_batch2_interleaved_qkv_and_custom_scale():
+    """Q, K, V are slices of one [b][t][Hq+2Hkv][d] tensor (non-trivial strides), batch 2, scale 0.2."""
+    import torch
+    import oracle
+    import paper_2505_19578_amd as sp
+    from synth import random_qkv
+    N, Hq, Hkv, d, B, scale = 512, 4, 2, 64, 64, 0.2
+    packs = []
+    for bb in range(2):
+        q, k, v = random_qkv(20 + bb, N, Hq, Hkv, d)
+        packs.append(np.concatenate([q, k, v], axis=1))
+    qkv = _dev(np.stack(packs))                        # [2][N][Hq+2Hkv][d]
+    q, k, v = qkv[:, :, :Hq], qkv[:, :, Hq:Hq + Hkv], qkv[:, :, Hq + Hkv:]
+    o_full = torch.zeros((2, N, Hq + 1, d), dtype=torch.bfloat16, device="cuda")   # padded head stride
+    o = o_full[:, :, :Hq]
+    shape = sp.shape_of(q, k, o, B, softmax_scale=scale)
+    nqb = N // B
+    ws = torch.empty(sp.sp_workspace_bytes(shape, 2), dtype=torch.uint8, device="cuda")
+    sc = torch.empty((2, 2, nqb, nqb), dtype=torch.float32, device="cuda")
+    idx = torch.empty((2, 2, nqb, nqb), dtype=torch.int32, device="cuda")
+    cnt = torch.empty((2, 2, nqb), dtype=torch.int32, device="cuda")
+    h2c, piv, gamma = [0, 1, 0, 1], [0, 1], 0.7
+    sp.sp_prefill_layer(shape, q, k, v, h2c, piv, gamma, o, sc, idx, cnt, ws)
+    torch.cuda.synchronize()
+    assert torch.all(o_full[:, :, Hq] == 0)            # the padding head slot is never written
+    for bb in range(2):
+        hq, hk, hv = (_f32(packs[bb][:, a:b]) for a, b in ((0, Hq), (Hq, Hq + Hkv), (Hq + Hkv, Hq + 2 * Hkv)))
+        idx_h, cnt_h = idx[bb].cpu().numpy(), cnt[bb].cpu().numpy()
+        ref = oracle.prefill_layer(hq, hk, hv, B, h2c, piv, gamma, scale=scale, masks=(idx_h, cnt_h))
+        assert np.abs(sc[bb].cpu().numpy() - ref["scores"]).max() <= 1e-3
+        for c in range(2):
+            i2, c2, _ = oracle.build_mask_rows(sc[bb, c].cpu().numpy(), gamma)
+            assert np.array_equal(i2, idx_h[c]) and np.array_equal(c2, cnt_h[c])
+        e = _err(o[bb].float().cpu().numpy(), ref["o"])
+        assert e[0] <= OUT_MAX and e[1] <= OUT_MEAN, e
+
+
+def test_sparse_call_with_caller_lists_and_unclustered_heads():
+    import torch
+    import oracle
+    import paper_2505_19578_amd as sp
+    from synth import random_qkv
+    N, Hq, Hkv, d, B = 1024, 4, 2, 128, 128
+    qb, kb, vb = random_qkv(31, N, Hq, Hkv, d)
+    q, k, v = (_dev(x).unsqueeze(0) for x in (qb, kb, vb))
+    hq, hk, hv = _f32(qb), _f32(kb), _f32(vb)
+    nqb = N // B
+    shape = sp.shape_of(q, k, None, B)
+    ws = torch.empty(sp.sp_workspace_bytes(shape, Hq), dtype=torch.uint8, device="cuda")
+    # three maps: all-ones, sink + diagonal, empty
+    idx = np.full((3, nqb, nqb), -1, np.int32)
+    cnt = np.zeros((3, nqb), np.int32)
+    for i in range(nqb):
+        idx[0, i, : i + 1] = np.arange(i + 1)
+        cnt[0, i] = i + 1
+        sel = sorted({0, i})
+        idx[1, i, : len(sel)] = sel
+        cnt[1, i] = len(sel)
+    o = torch.full_like(q, 7.0)
+    sp.sp_block_sparse_attn(shape, q, k, v, [3, 0, 2], [0, 1, 2], torch.from_numpy(idx).cuda().unsqueeze(0),
+                            torch.from_numpy(cnt).cuda().unsqueeze(0), 3, o, ws)
+    torch.cuda.synchronize()
+    og = o.float().cpu().numpy()[0]
+    assert np.all(og[:, 1] == 7.0)                                       # head 1 not listed: untouched
+    assert np.all(og[:, 2] == 0.0)                                       # empty lists: zeros
+    dense3, _, _ = oracle.dense_rows(hq[:, 3], hk[:, 1], hv[:, 1], B)
+    e = _err(og[:, 3], dense3)
+    assert e[0] <= OUT_MAX and e[1] <= OUT_MEAN                          # all-ones pattern == dense attention
+    ref0 = oracle.masked_rows(hq[:, 0], hk[:, 0], hv[:, 0], B, idx[1], cnt[1])
+    e = _err(og[:, 0], ref0)
+    assert e[0] <= OUT_MAX and e[1] <= OUT_MEAN
+    # the dense call on the same head gives the same bits as the all-ones sparse call? not required; but
+    # a head outside every cluster must come out dense in the fused call
+    o2 = torch.zeros_like(q)
+    sc = torch.empty((1, 1, nqb, nqb), dtype=torch.float32, device="cuda")
+    ix = torch.empty((1, 1, nqb, nqb), dtype=torch.int32, device="cuda")
+    ct = torch.empty((1, 1, nqb), dtype=torch.int32, device="cuda")
+    sp.sp_prefill_layer(shape, q, k, v, [0, 0, -1, -1], [0], 0.9, o2, sc, ix, ct, ws)
+    torch.cuda.synchronize()
+    o2h = o2.float().cpu().numpy()[0]
+    for h in (2, 3):
+        dn, _, _ = oracle.dense_rows(hq[:, h], hk[:, h // 2], hv[:, h // 2], B)
+        e = _err(o2h[:, h], dn)
+        assert e[0] <= OUT_MAX and e[1] <= OUT_MEAN
+    m1 = oracle.masked_rows(hq[:, 1], hk[:, 0], hv[:, 0], B, ix.cpu().numpy()[0, 0], ct.cpu().numpy()[0, 0])
+    e = _err(o2h[:, 1], m1)
+    assert e[0] <= OUT_MAX and e[1] <= OUT_MEAN
+
+
+@pytest.mark.parametrize("nkb,n_maps", [(1, 2), (7, 3), (64, 2), (200, 2), (256, 1), (257, 2), (1000, 1), (1024, 1),
+                                        (1500, 1), (4096, 1)])
+def test_mask_builder_all_paths_bit_exact(nkb, n_maps):
+    """Random, tied, one-hot, zero, NaN, negative and > 1 scores; every register / re-read code path."""
+    import torch
+    import oracle
+    import paper_2505_19578_amd as sp
+    rng = np.random.default_rng(nkb)
+    sc = np.tril(rng.random((n_maps, nkb, nkb)).astype(np.float32) ** 8)
+    sc /= np.maximum(sc.sum(-1, keepdims=True), 1e-30)
+    sc = sc.astype(np.float32)
+    if nkb >= 7:
+        sc[0, 3, :4] = 0.25                       # exact four-way tie
+        sc[0, 4, :5] = 0.0                        # all-zero row
+        sc[0, 5, :6] = [0, 0, 1.0, 0, 0, 0]       # one-hot
+        sc[0, 6, :7] = [np.nan, -1.0, 2.0, 0.125, 0.125, np.inf, 0.0625]
+    if nkb >= 200:
+        sc[-1, 150, :151] = np.float32(1.0 / 256)  # 151-way tie
+    for gamma in (0.5, 0.9, 1.0):
+        dsc = torch.from_numpy(sc).cuda()
+        idx = torch.empty((n_maps, nkb, nkb), dtype=torch.int32, device="cuda")
+        cnt = torch.empty((n_maps, nkb), dtype=torch.int32, device="cuda")
+        bm = torch.empty((n_maps, nkb, (nkb + 63) // 64), dtype=torch.int64, device="cuda")
+        sp.sp_build_block_mask(dsc, n_maps, nkb, nkb, gamma, idx, cnt, bm)
+        torch.cuda.synchronize()
+        idx_h, cnt_h, bm_h = idx.cpu().numpy(), cnt.cpu().numpy(), bm.cpu().numpy().view(np.uint64)
+        for mm in range(n_maps):
+            i2, c2, _ = oracle.build_mask_rows(sc[mm], gamma)
+            assert np.array_equal(c2, cnt_h[mm]), (nkb, gamma, mm)
+            assert np.array_equal(i2, idx_h[mm]), (nkb, gamma, mm)
+        # bitmask == the lists, bit j % 64 of word j / 64
+        rows = rng.integers(0, nkb, size=min(nkb, 16))
+        for i in rows:
+            bits = np.zeros(((nkb + 63) // 64) * 64, dtype=bool)
+            bits[idx_h[0, i, : cnt_h[0, i]]] = True
+            words = np.packbits(bits.reshape(-1, 64)[:, ::-1], axis=1).view(">u8").reshape(-1)
+            assert np.array_equal(words.astype(np.uint64), bm_h[0, i])
+
+
+def test_run_to_run_determinism():
+    import torch
+    import paper_2505_19578_amd as sp
+    from synth import CONFIGS, make_layer
+    L = make_layer(CONFIGS["llama8b_32k"], seq=4096)
+    cfg = L["cfg"]
+    q, k, v = (_dev(L[x]).unsqueeze(0) for x in "qkv")
+    nqb, C = cfg.seq // cfg.block, cfg.n_clusters
+    shape = sp.shape_of(q, k, None, cfg.block)
+    ws = torch.empty(sp.sp_workspace_bytes(shape, C), dtype=torch.uint8, device="cuda")
+    outs = []
+    for _ in range(3):
+        o = torch.zeros_like(q)
+        sc = torch.empty((1, C, nqb, nqb), dtype=torch.float32, device="cuda")
+        idx = torch.empty((1, C, nqb, nqb), dtype=torch.int32, device="cuda")
+        cnt = torch.empty((1, C, nqb), dtype=torch.int32, device="cuda")
+        ws.random_(0, 255)                                  # stale workspace contents must not matter
+        sp.sp_prefill_layer(shape, q, k, v, L["head_to_cluster"], L["pivot_heads"], cfg.gamma, o, sc, idx, cnt, ws)
+        torch.cuda.synchronize()
+        outs.append((o.view(torch.int16).clone(), sc.clone(), idx.clone(), cnt.clone()))
+    for a in outs[1:]:
+        for x, y in zip(outs[0], a):
+            assert torch.equal(x, y)
