@@ -220,6 +220,18 @@ __device__ __forceinline__ void static_for(F &&f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
+// Reference point of the online softmax.  The running reference m only has to stay within
+// SP_MAX_SLACK (log2 units) of the true running max: P = 2^(x - m) is then at most 2^SP_MAX_SLACK,
+// harmless in fp32 / bf16, and m, l, the block sums and O stay mutually consistent whatever m is.
+// Moving m only when the max outgrows it by more than the slack makes O rescaling rare (a lane
+// triggers it a handful of times per row instead of at every new maximum).
+#ifndef SP_MAX_SLACK
+#define SP_MAX_SLACK 8.0f
+#endif
+__device__ __forceinline__ float lazy_max(float m_ref, float tile_max) {
+  return (tile_max > m_ref + SP_MAX_SLACK) ? tile_max : m_ref;
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 t = {a, b};
   bf16x2 r = __builtin_convertvector(t, bf16x2);
@@ -395,7 +407,7 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
 #pragma unroll
       for (int r = (rb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[rb][r], s[rb][r + 1]));
     mx = max_xor32(mx);
-    const float m_new = fmaxf(m, mx * p.c);
+    const float m_new = lazy_max(m, mx * p.c);
     const float alpha = fast_exp2(m - m_new);
     m = m_new;
     l *= alpha;
@@ -574,7 +586,7 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
         }
         if (np == NP - SP_MAXTAIL) {
           mx = max_xor32(mx);
-          const float m_new = fmaxf(m, mx * p.c);
+          const float m_new = lazy_max(m, mx * p.c);
           alpha = fast_exp2(m - m_new);
           m = m_new;
           l *= alpha;
@@ -718,6 +730,25 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
   }
 }
 
+// MFMA issued from inline assembly, used by the wide kernel: it pins the register files (S tiles in
+// architectural VGPRs where the VALU reads them without copies; O and Q in accumulation VGPRs),
+// which the builtin form cannot do once a kernel uses more than 256 registers.  The compiler does not
+// see these as MFMAs, so the kernel keeps the required distance between an MFMA and any other
+// instruction that touches its result itself (mfma_drain before the VALU / memory code reads S or O).
+__device__ __forceinline__ void mfma_s0(f32x16 &acc, const bf16x8 &a, const bf16x8 &bq) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(bq));
+}
+__device__ __forceinline__ void mfma_s(f32x16 &acc, const bf16x8 &a, const bf16x8 &bq) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(bq));
+}
+__device__ __forceinline__ void mfma_o(f32x16 &acc, const bf16x8 &a, const bf16x8 &bp) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(bp));
+}
+// 80 idle issue cycles: every MFMA issued before it (two can still be queued) has written its result
+__device__ __forceinline__ void mfma_drain() {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+}
+
 // ---------------------------------------------------------------------------------------------
 // attention kernel, wide variant (block = 128): 64 queries per wavefront, one wavefront per SIMD
 // ---------------------------------------------------------------------------------------------
@@ -767,16 +798,32 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
   bf16x8 qf[2][DS];
 #pragma unroll
   for (int qh = 0; qh < 2; ++qh) {
-    if (active) {
-      const uint16_t *qp =
-          p.q + (int64_t)b * p.q_sb + ((int64_t)ib * B + tq[qh]) * p.q_st + (int64_t)head * p.q_sh + 8 * h;
-#pragma unroll
-      for (int ds = 0; ds < DS; ++ds) qf[qh][ds] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
+    // Q fragments go straight into accumulation VGPRs and are defined by this statement alone (idle
+    // wave groups read a valid row too), so they stay there for the whole kernel; the wait sits in
+    // the same statement because the compiler treats the outputs as valid as soon as it ends.
+    const int head_ld = head >= 0 ? head : p.head_a[slot];
+    const int ib_ld = ib < p.nqb ? ib : p.nqb - 1;
+    const uint16_t *qp =
+        p.q + (int64_t)b * p.q_sb + ((int64_t)ib_ld * B + tq[qh]) * p.q_st + (int64_t)head_ld * p.q_sh + 8 * h;
+    if constexpr (DS == 8) {
+      asm volatile(
+          "global_load_dwordx4 %0, %8, off\n\tglobal_load_dwordx4 %1, %8, off offset:32\n\t"
+          "global_load_dwordx4 %2, %8, off offset:64\n\tglobal_load_dwordx4 %3, %8, off offset:96\n\t"
+          "global_load_dwordx4 %4, %8, off offset:128\n\tglobal_load_dwordx4 %5, %8, off offset:160\n\t"
+          "global_load_dwordx4 %6, %8, off offset:192\n\tglobal_load_dwordx4 %7, %8, off offset:224\n\t"
+          "s_waitcnt vmcnt(0)"
+          : "=&a"(qf[qh][0]), "=&a"(qf[qh][1]), "=&a"(qf[qh][2]), "=&a"(qf[qh][3]), "=&a"(qf[qh][4]),
+            "=&a"(qf[qh][5]), "=&a"(qf[qh][6]), "=&a"(qf[qh][7])
+          : "v"(qp)
+          : "memory");
     } else {
-#pragma unroll
-      for (int ds = 0; ds < DS; ++ds)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[qh][ds][e] = (__bf16)0.f;
+      asm volatile(
+          "global_load_dwordx4 %0, %4, off\n\tglobal_load_dwordx4 %1, %4, off offset:32\n\t"
+          "global_load_dwordx4 %2, %4, off offset:64\n\tglobal_load_dwordx4 %3, %4, off offset:96\n\t"
+          "s_waitcnt vmcnt(0)"
+          : "=&a"(qf[qh][0]), "=&a"(qf[qh][1]), "=&a"(qf[qh][2]), "=&a"(qf[qh][3])
+          : "v"(qp)
+          : "memory");
     }
   }
   f32x16 oacc[2][DB];
@@ -826,28 +873,34 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
 #pragma unroll
     for (int n = 0; n < CH; ++n) lds_dma16(src + n * 1024, lane * 16, slot_base + (w * CH + n) * 1024);
   };
+#ifdef DIAG_TIMING
+  unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
+  unsigned long long tmark = 0;
+#endif
   auto sync_and_fill = [&](int t, int jv, int jk) {
+    TMARK(5);
     wait_vm<VM_KEEP>();
+    TMARK(0);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    TMARK(1);
     issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
     issue_img(t + DK, jk, false, lds_k + ((t + DK) % RK) * IMG);
+    TMARK(2);
   };
 
   // ---- building blocks of the general (near-diagonal) step, one 32-query half at a time ----
   auto qk_half = [&](const char *kbuf, int qh, f32x16(&s)[2]) {
     const char *kb = kbuf + lane * 16;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
-#pragma unroll
     for (int ds = 0; ds < DS; ++ds)
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
         const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kb + (rb * DS + ds) * 1024);
-        s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qh][ds], s[rb], 0, 0, 0);
+        if (ds == 0) mfma_s0(s[rb], a, qf[qh][ds]);
+        else mfma_s(s[rb], a, qf[qh][ds]);
       }
+    mfma_drain();
   };
   auto max_half = [&](f32x16(&s)[2], int qh, int mode, int sub) -> float {
     if (mode == 1) {
@@ -865,7 +918,7 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
 #pragma unroll
       for (int r = (rb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[rb][r], s[rb][r + 1]));
     mx = max_xor32(mx);
-    const float m_new = fmaxf(m[qh], mx * p.c);
+    const float m_new = lazy_max(m[qh], mx * p.c);
     const float alpha = fast_exp2(m[qh] - m_new);
     m[qh] = m_new;
     l[qh] *= alpha;
@@ -907,8 +960,9 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vb + (db * 4 + ks) * 1024);
-        oacc[qh][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks], oacc[qh][db], 0, 0, 0);
+        mfma_o(oacc[qh][db], a, pb[ks]);
       }
+    mfma_drain();
   };
 
   // fast step: tiles t and t+1 off the diagonal for every wavefront.  Hand-laid schedule of
@@ -944,18 +998,11 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
       if constexpr (qh == 0 && f + PF < NF) fr[(f + PF) % (PF + 1)] = frag(f + PF);
       if constexpr (n < NQ) {
         constexpr int rb = f % 2, ds = f / 2;
-        if constexpr (f < 2) {
-          f32x16 z;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) z[r] = 0.f;
-          s_next[qh][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % (PF + 1)], qf[qh][ds], z, 0, 0, 0);
-        } else {
-          s_next[qh][rb] =
-              __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % (PF + 1)], qf[qh][ds], s_next[qh][rb], 0, 0, 0);
-        }
+        if constexpr (f < 2) mfma_s0(s_next[qh][rb], fr[f % (PF + 1)], qf[qh][ds]);
+        else mfma_s(s_next[qh][rb], fr[f % (PF + 1)], qf[qh][ds]);
       } else {
         constexpr int fp = f - NFQ, ks = fp / DB, db = fp % DB;
-        oacc[qh][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[f % (PF + 1)], pb[qh][ks], oacc[qh][db], 0, 0, 0);
+        mfma_o(oacc[qh][db], fr[f % (PF + 1)], pb[qh][ks]);
       }
       // exp units: u = 8 ks + 4 qh' + e2, two scores each, unit u rides in group u * NEXP / 32
       constexpr int u_lo = (32 * n + NEXP - 1) / NEXP, u_hi = (32 * (n + 1) + NEXP - 1) / NEXP;
@@ -996,7 +1043,7 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
       if constexpr (n == NM - 4 || n == NM - 3) {
         constexpr int q2 = n - (NM - 4);
         const float mq = max_xor32(mx[q2]);
-        const float m_new = fmaxf(m[q2], mq * p.c);
+        const float m_new = lazy_max(m[q2], mq * p.c);
         alpha[q2] = fast_exp2(m[q2] - m_new);
         m[q2] = m_new;
         l[q2] *= alpha[q2];
@@ -1004,12 +1051,15 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
       }
       __builtin_amdgcn_sched_barrier(0);
     });
+    TMARK(3);
+    if (__any(alpha[0] != 1.f || alpha[1] != 1.f)) mfma_drain();  // O is about to be read by the VALU
     rescale_half(0, alpha[0]);
     rescale_half(1, alpha[1]);
     if (SCORES && t % SPB == SPB - 1 && h == 0) {
       lrow[(int64_t)j0 * B] = lval[0];
       lrow[(int64_t)j0 * B + 32] = lval[1];
     }
+    TMARK(4);
   };
   // general step: per-half causal mask / skip near the diagonal, optional next tile
   auto slow_step = [&](int t, int j0, int j1, int jv, int jk, f32x16(&s_cur)[2][2], f32x16(&s_next)[2][2]) {
@@ -1092,9 +1142,18 @@ __global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
       jw[5] = jn1;
     }
     wait_vm<0>();  // drain the ring's look-ahead loads before the LDS is reused or released
+#ifdef DIAG_TIMING
+    if (lane == 0 && p.dbg) {
+      unsigned long long *d = p.dbg + ((size_t)blockIdx.x * NWT + w) * 8;
+      for (int k = 0; k < 6; ++k) d[k] = tacc[k];
+      d[6] = nsub;
+      d[7] = nfast;
+    }
+#endif
   }
 
   // ---- output: O = O^T accumulators / l, rounded to bf16 ----
+  mfma_drain();
   if (active) {
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {

@@ -63,6 +63,7 @@ class LayerConfig:
     sink_boost: float = 4.0    # logit boost of key 0
     heavy_boost: float = 10.0  # logit boost of the heavy vertical keys
     value_gain: float = 4.0    # topic-dependent mean of V (nu)
+    value_noise: float = 0.5   # std of the i.i.d. part of V (keeps |O| < 4, where one bf16 ulp is 2^-6)
 
     @property
     def cluster_size(self) -> int:
@@ -171,7 +172,7 @@ def make_layer(cfg: LayerConfig, layer: int = 0, seq: Optional[int] = None,
     for kv in range(Hkv):
         cl = sorted({int(h2c[h]) for h in range(kv * G, (kv + 1) * G)})
         x = _rng(seed, 2, kv).standard_normal((N, d), dtype=np.float32)
-        y = _rng(seed, 3, kv).standard_normal((N, d), dtype=np.float32)
+        y = cfg.value_noise * _rng(seed, 3, kv).standard_normal((N, d), dtype=np.float32)
         for c in cl:
             x += (g * A[c])[topics[c]]
             y += (cfg.value_gain * A2[c])[topics[c]]
