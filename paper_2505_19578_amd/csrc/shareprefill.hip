@@ -24,7 +24,6 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <utility>
 #include <cmath>
 #include <cstdarg>
 #include <cstdint>
@@ -47,10 +46,6 @@ constexpr int SP_MAX_HEADS = 128;
 constexpr int KT = 64;  // keys per sub-tile
 
 thread_local char g_err[512] = "";
-#ifdef DIAG_TIMING
-unsigned long long *g_dbg_store = nullptr;
-unsigned long long *g_dbg_ptr() { return g_dbg_store; }
-#endif
 
 // Optional per-kernel timing (sp_profile_enable / sp_profile_read): every launch is bracketed
 // by two HIP events on the caller's stream.  Process-wide, not thread-safe; meant for benches.
@@ -149,29 +144,6 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(PackParams p) {
 // attention kernel
 // ---------------------------------------------------------------------------------------------
 constexpr int SP_MAX_SLOTS = SP_MAX_HEADS + 8;
-// scheduler-hint knobs of the fast step (per MFMA: 1 LDS read and SGB_V VALU instructions)
-#ifndef SGB_N
-#define SGB_N 1
-#endif
-#ifndef SP_DK1
-#define SP_DK1 2
-#endif
-#ifndef SP_DV1
-#define SP_DV1 1
-#endif
-#ifndef SP_MAXTAIL
-#define SP_MAXTAIL 4
-#endif
-#ifndef SP_PRIO
-#define SP_PRIO 0
-#endif
-#ifndef SGB_PRE
-#define SGB_PRE 4
-#endif
-#ifndef SGB_V
-#define SGB_V 5
-#endif
-
 struct AttnParams {
   const uint16_t *q;
   const char *kvp;  // packed K/V images
@@ -179,19 +151,14 @@ struct AttnParams {
   int64_t q_sb, q_st, q_sh, o_sb, o_st, o_sh;
   int seq, nqb, n_kv_heads, group, n_heads, n_maps;
   int ncol;   // slots per XCD: workgroup -> slot table below, 8 * ncol entries
-  int nrows;  // workgroup rows per slot (query blocks, or pairs of them)
   float c;    // softmax scale * log2(e)
   float *lws;     // dense: block-local log2-sum-exp [b][n][nqb][nkb][B], or null
   float *scores;  // dense: [b][n][nqb][nkb], or null
   const int32_t *kb_idx;  // sparse: [b][n_maps][nqb][nkb]
   const int32_t *kb_cnt;  // sparse: [b][n_maps][nqb]
-#ifdef DIAG_TIMING
-  unsigned long long *dbg;
-#endif
-  int32_t head_a[SP_MAX_SLOTS];    // query head of wave group 0, -1 = padding slot
-  int32_t head_b[SP_MAX_SLOTS];    // query head of wave group 1 (two-group kernels), -1 = none
-  int32_t head_map[SP_MAX_SLOTS];  // sparse: which list the slot's heads use
-  int32_t pos_a[SP_MAX_SLOTS];     // position of head_a in the caller's list (scores / lws index)
+  int32_t head_ids[SP_MAX_SLOTS];  // query head of each slot, -1 = padding slot
+  int32_t head_map[SP_MAX_SLOTS];  // sparse: which list the slot's head uses
+  int32_t head_pos[SP_MAX_SLOTS];  // position of the head in the caller's list (scores / lws index)
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -209,25 +176,12 @@ __device__ __forceinline__ float sum_xor32(float x) {
   return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
 }
 
-// compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1, so that every index derived
-// from I is a constant expression (register arrays never get a run-time subscript)
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f) {
-  static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
 // Reference point of the online softmax.  The running reference m only has to stay within
 // SP_MAX_SLACK (log2 units) of the true running max: P = 2^(x - m) is then at most 2^SP_MAX_SLACK,
 // harmless in fp32 / bf16, and m, l, the block sums and O stay mutually consistent whatever m is.
 // Moving m only when the max outgrows it by more than the slack makes O rescaling rare (a lane
 // triggers it a handful of times per row instead of at every new maximum).
-#ifndef SP_MAX_SLACK
-#define SP_MAX_SLACK 8.0f
-#endif
+constexpr float SP_MAX_SLACK = 8.0f;
 __device__ __forceinline__ float lazy_max(float m_ref, float tile_max) {
   return (tile_max > m_ref + SP_MAX_SLACK) ? tile_max : m_ref;
 }
@@ -239,9 +193,9 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 
 // One wavefront-wide 1 KiB copy HBM/L2 -> LDS without passing through registers: lane l moves the
-// 16 bytes at g_uniform + lane_off to LDS byte address lds_base + 16 l (g_uniform, lds_base wave-uniform).  Issued from inline
-// assembly so that the compiler does not serialise it against the kernel's own LDS reads; the
-// kernel counts these loads itself (wait_vm).
+// 16 bytes at g_uniform + lane_off to LDS byte address lds_base + 16 l (g_uniform and lds_base are
+// wave-uniform).  Issued from inline assembly so that the compiler does not serialise it against
+// the kernel's own LDS reads; the kernel counts these loads itself (wait_vm).
 __device__ __forceinline__ void lds_dma16(const void *g_uniform, uint32_t lane_off, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(lane_off),
                "s"(g_uniform)
@@ -257,69 +211,54 @@ __device__ __forceinline__ void wait_vm() {
 // Software pipeline (per wavefront), step t:
 //     MFMA stream   S[t+1] = K[t+1] Q^T          then   O += V[t]^T P[t]^T
 //     VALU stream   P[t] = 2^(S[t] c - m)        then   row max of S[t+1], running-max update
-//   interleaved instruction by instruction (scheduler hints), so the softmax runs in the shadow
-//   of the matrix pipe.  Steps near the diagonal take a general path (causal mask / skip).
+//   interleaved instruction by instruction (a hand-laid schedule), so the softmax runs in the
+//   shadow of the matrix pipe.  Steps near the diagonal take a general path (causal mask / skip).
 // K and V images ride in LDS rings (RK, RV slots) filled by LDS-direct loads issued DK resp. DV
 // steps ahead; one workgroup barrier per step.
-// NG = 1: one query block per workgroup (B/32 wavefronts), 2 workgroups per CU.
-// NG = 2: two wave groups share every K/V image: two consecutive query blocks of one head (dense)
-//         or one query block of two heads that use the same list (sparse); 1 workgroup per CU,
-//         deeper rings.
-template <int D, int B, int NG, bool DENSE, bool SCORES>
-__global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_kernel(AttnParams p) {
-  constexpr int NW = B / 32;        // wavefronts per group, 32 queries each
-  constexpr int NWT = NW * NG;      // wavefronts per workgroup
+// One query block per workgroup (B/32 wavefronts); two workgroups per CU, so each SIMD holds two
+// wavefronts of different workgroups and one's barrier / load-issue time is covered by the other.
+template <int D, int B, bool DENSE, bool SCORES>
+__global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
+  constexpr int NW = B / 32;        // wavefronts per workgroup, 32 queries each
   constexpr int SPB = B / KT;       // sub-tiles per key block
   constexpr int IMG = KT * D * 2;   // bytes of a packed K (or V) image
   constexpr int STAGE = 2 * IMG;    // K image + V image in the packed buffer
   constexpr int DS = D / 16;        // k-steps of the QK^T product
   constexpr int DB = D / 32;        // 32-row blocks of O^T
-  constexpr int DK = NG == 2 ? 4 : SP_DK1, DV = NG == 2 ? 3 : SP_DV1;  // prefetch distances (steps)
+  constexpr int DK = 2, DV = 1;                              // prefetch distances (steps)
   constexpr int RK = DK, RV = DV + 1;                        // ring slots
-  constexpr int CH = IMG / 1024 / NWT;                       // 1 KiB chunks per wavefront per image
+  constexpr int CH = IMG / 1024 / NW;                        // 1 KiB chunks per wavefront per image
   // loads that may still be in flight at the top of a step (each step issues CH for V, then CH for K)
   constexpr int VM_KEEP = ((2 * DV - 1) < (2 * DK - 4) ? (2 * DV - 1) : (2 * DK - 4)) * CH;
-  static_assert(IMG % (1024 * NWT) == 0, "image must split evenly over the wavefronts");
-#ifndef SP_LDS_PAD
-#define SP_LDS_PAD 0
-#endif
-  __shared__ __attribute__((aligned(1024))) char smem[(RK + RV) * IMG + SP_LDS_PAD];
+  static_assert(IMG % (1024 * NW) == 0, "image must split evenly over the wavefronts");
+  __shared__ __attribute__((aligned(1024))) char smem[(RK + RV) * IMG];
   const uint32_t lds_k = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
   const uint32_t lds_v = lds_k + RK * IMG;
 
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, c32 = lane & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, kept scalar
-  const int g = w / NW, wg = w % NW;                        // wave group, wavefront inside the group
-  // workgroup -> (XCD, column, row, batch): workgroups are dealt round-robin to the 8 XCDs, so slot
-  // table row x lists the heads XCD x works on (heads that share a KV head sit on one XCD and meet in
-  // its L2); long rows first.
+  // workgroup -> (XCD, column, query block, batch): workgroups are dealt round-robin to the 8 XCDs,
+  // so slot table row x lists the heads XCD x works on (heads that share a KV head sit on one XCD
+  // and meet in its L2); long rows first.
   const int xcd = blockIdx.x & 7;
   int rest = blockIdx.x >> 3;
   const int slot = xcd * p.ncol + rest % p.ncol;
   rest /= p.ncol;
-  const int row = p.nrows - 1 - (rest % p.nrows);
-  const int b = rest / p.nrows;
-  if (p.head_a[slot] < 0) return;
+  const int i = p.nqb - 1 - (rest % p.nqb);
+  const int b = rest / p.nqb;
+  const int head = p.head_ids[slot];
+  if (head < 0) return;  // padding slot
   const int nkb = p.nqb;
-  // this wave group's head and query block; idiag = the workgroup's last key block (dense)
-  const int head = (NG == 2 && !DENSE && g == 1) ? p.head_b[slot] : p.head_a[slot];
-  const int ib = (NG == 2 && DENSE) ? 2 * row + g : row;
-  const bool active = head >= 0 && ib < p.nqb;
-  const int hpos = p.pos_a[slot];
-  const int kvh = p.head_a[slot] / p.group;
+  const int hpos = p.head_pos[slot];
+  const int kvh = head / p.group;
 
-  const int tq = 32 * wg + c32;  // this lane's query inside the block
+  const int tq = 32 * w + c32;  // this lane's query inside the block
   bf16x8 qf[DS];
-  if (active) {
+  {
     const uint16_t *qp =
-        p.q + (int64_t)b * p.q_sb + ((int64_t)ib * B + tq) * p.q_st + (int64_t)head * p.q_sh + 8 * h;
+        p.q + (int64_t)b * p.q_sb + ((int64_t)i * B + tq) * p.q_st + (int64_t)head * p.q_sh + 8 * h;
 #pragma unroll
     for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
-  } else {
-#pragma unroll
-    for (int ds = 0; ds < DS; ++ds)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[ds][e] = (__bf16)0.f;
   }
 
   f32x16 oacc[DB];
@@ -332,9 +271,9 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
   int nblk;
   const int32_t *list = nullptr;
   if (DENSE) {
-    nblk = (NG == 2) ? ((2 * row + 1 < p.nqb) ? 2 * row + 2 : 2 * row + 1) : row + 1;
+    nblk = i + 1;
   } else {
-    const int64_t lrow_id = ((int64_t)b * p.n_maps + p.head_map[slot]) * p.nqb + row;
+    const int64_t lrow_id = ((int64_t)b * p.n_maps + p.head_map[slot]) * p.nqb + i;
     nblk = p.kb_cnt[lrow_id];
     nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
     list = p.kb_idx + lrow_id * nkb;
@@ -342,21 +281,20 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
   const int nsub = nblk * SPB;
   const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
   float *lrow = nullptr;
-  if (SCORES) lrow = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb) * B + tq;
+  if (SCORES) lrow = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb) * B + tq;
 
-  // key block of sub-tile t (t clamped to the sequence; list entries clamped into [0, row]: memory-safe
+  // key block of sub-tile t (t clamped to the sequence; list entries clamped into [0, i]: memory-safe
   // whatever the list holds)
   auto block_of = [&](int t) -> int {
     int e = (t < nsub ? t : nsub - 1) / SPB;
     if (DENSE) return e;
     const int j = list[e];
-    return j < 0 ? 0 : (j > row ? row : j);
+    return j < 0 ? 0 : (j > i ? i : j);
   };
   // what this wavefront has to do for sub-tile `sub` of key block j: 0 all of it, 1 causal mask, 2 nothing
   auto mode_of = [&](int j, int sub) -> int {
-    if (!active || j > ib) return 2;
-    if (j != ib) return 0;
-    const int klo = KT * sub, qlo = 32 * wg;
+    if (j != i) return 0;
+    const int klo = KT * sub, qlo = 32 * w;
     return (klo > qlo + 31) ? 2 : ((klo + KT - 1 <= qlo) ? 0 : 1);
   };
   // every wavefront moves CH chunks of the image of sub-tile t (clamped) into ring slot `slot_base`
@@ -424,12 +362,8 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {
         const int r = 8 * (ks & 1) + 2 * e2;
-#ifdef DIAG_NO_SOFTMAX
-        const float p0 = s[ks >> 1][r], p1 = s[ks >> 1][r + 1];
-#else
         const float p0 = fast_exp2(__builtin_fmaf(s[ks >> 1][r], p.c, -m));
         const float p1 = fast_exp2(__builtin_fmaf(s[ks >> 1][r + 1], p.c, -m));
-#endif
         rs0 += p0;
         rs1 += p1;
         t[e2] = pack_bf16(p0, p1);
@@ -464,59 +398,26 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
   // the K image (tile t+DK).
   // sync_and_fill: wait until the images this step reads have landed for every wavefront, then
   // refill the ring slots the previous step freed.
-#ifdef DIAG_TIMING
-  unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
-  unsigned long long tmark = 0;
-#define TMARK(k) do { const unsigned long long now_ = __builtin_readcyclecounter(); tacc[k] += now_ - tmark; tmark = now_; } while (0)
-#else
-#define TMARK(k) do { } while (0)
-#endif
-  auto sync_and_fill = [&](int t, int jv, int jk, bool fill = true) {
-    TMARK(5);
+  auto sync_and_fill = [&](int t, int jv, int jk) {
     wait_vm<VM_KEEP>();
-    TMARK(0);
-#ifndef DIAG_NO_BARRIER
     __builtin_amdgcn_s_barrier();
-#endif
     asm volatile("" ::: "memory");
-    TMARK(1);
-#ifndef DIAG_NO_LOAD
-    if (fill) {
-      issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
-      issue_img(t + DK, jk, false, lds_k + ((t + DK) % RK) * IMG);
-    }
-#endif
-    TMARK(2);
+    issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
+    issue_img(t + DK, jk, false, lds_k + ((t + DK) % RK) * IMG);
   };
-  // fast step: tiles t and t+1 both off the diagonal (for every wave group).  One basic block up to
-  // the rescale test.
+  // fast step: tiles t and t+1 both off the diagonal.  One basic block up to the rescale test.
   auto fast_step = [&](int t, int j0, int jv, int jk, f32x16(&s_cur)[2], f32x16(&s_next)[2]) {
-#ifdef SP_SPREAD_LOADS
-    sync_and_fill(t, jv, jk, false);
-    const char *src_v = img_src(t + DV, jv, true), *src_k = img_src(t + DK, jk, false);
-    const uint32_t dst_v = lds_v + ((t + DV) % RV) * IMG, dst_k = lds_k + ((t + DK) % RK) * IMG;
-    if (!active) {
-#pragma unroll
-      for (int n = 0; n < CH; ++n) issue_chunk(src_v, dst_v, n);
-#pragma unroll
-      for (int n = 0; n < CH; ++n) issue_chunk(src_k, dst_k, n);
-      return;
-    }
-#else
     sync_and_fill(t, jv, jk);
-    if (!active) return;
-#endif
     const char *kb = smem + ((t + 1) % RK) * IMG + lane * 16;
     const char *vb = smem + (RK + t % RV) * IMG + lane * 16;
     // Hand-laid schedule: NM groups, each = one MFMA + one LDS read (PF fragments ahead) + a slice
     // of the VALU work; nothing may cross a group boundary (sched_barrier).
     //   groups 0 .. NQ-1   : S[t+1] += K frag * Q frag ; exp / row-sum / bf16 pack of S[t]
     //   groups NQ .. NM-1  : O += V frag * P frag       ; row max of S[t+1], running-max update
-    constexpr int NQ = 2 * DS, NP = 4 * DB, NM = NQ + NP, PF = SGB_PRE;
+    constexpr int NQ = 2 * DS, NP = 4 * DB, NM = NQ + NP;
+    constexpr int PF = 4;       // LDS fragments read ahead of the MFMA that uses them
+    constexpr int MAXTAIL = 4;  // the running-max update sits this many groups before the end
     auto frag = [&](int n) -> bf16x8 {
-#ifdef DIAG_NO_LDSREAD
-      return qf[n % DS];
-#endif
       if (n < NQ) return *reinterpret_cast<const bf16x8 *>(kb + ((n % 2) * DS + n / 2) * 1024);
       const int np = n - NQ;
       return *reinterpret_cast<const bf16x8 *>(vb + ((np % DB) * 4 + np / DB) * 1024);
@@ -525,19 +426,11 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
     bf16x8 pb[4];
     u32x4 pt;
     float rs0 = 0.f, rs1 = 0.f, mx = 0.f, lval = 0.f, alpha = 1.f;
+    float xa[16], xb[16];
 #pragma unroll
     for (int n = 0; n < PF; ++n) fr[n] = frag(n);
-    if (SP_PRIO) __builtin_amdgcn_s_setprio(SP_PRIO);
 #pragma unroll
     for (int n = 0; n < NM; ++n) {
-#ifdef SP_SPREAD_LOADS
-      // the step's 2*CH LDS-direct loads, one every NM / (2*CH) groups (V image first, then K)
-      if (n % (NM / (2 * CH)) == 0) {
-        const int q_ = n / (NM / (2 * CH));
-        if (q_ < CH) issue_chunk(src_v, dst_v, q_);
-        else if (q_ < 2 * CH) issue_chunk(src_k, dst_k, q_ - CH);
-      }
-#endif
       if (n + PF < NM) fr[(n + PF) % (PF + 1)] = frag(n + PF);
       if (n < NQ) {
         if (n < 2) {
@@ -548,43 +441,49 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
         } else {
           s_next[n % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], qf[n / 2], s_next[n % 2], 0, 0, 0);
         }
-        // exp units u (2 scores each) that belong to this group
+      }
+      // exp units u (2 scores each), three stages in consecutive groups so that no instruction waits
+      // on the one just issued: scale+shift in group g(u), exp2 in g(u)+1, row sum + bf16 pack in g(u)+2
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          if (u * NQ / 16 != n) continue;
-          const int ks = u / 4, e2 = u % 4, r = 8 * (ks & 1) + 2 * e2;
-#ifdef DIAG_NO_SOFTMAX
-          const float p0 = s_cur[ks >> 1][r], p1 = s_cur[ks >> 1][r + 1];
-#else
-          const float p0 = fast_exp2(__builtin_fmaf(s_cur[ks >> 1][r], p.c, -m));
-          const float p1 = fast_exp2(__builtin_fmaf(s_cur[ks >> 1][r + 1], p.c, -m));
-#endif
-          rs0 += p0;
-          rs1 += p1;
-          pt[e2] = pack_bf16(p0, p1);
+      for (int u = 0; u < 16; ++u) {
+        const int gu = u * NQ / 16;
+        const int ks = u / 4, e2 = u % 4, r = 8 * (ks & 1) + 2 * e2;
+        if (gu == n) {
+          xa[u] = __builtin_fmaf(s_cur[ks >> 1][r], p.c, -m);
+          xb[u] = __builtin_fmaf(s_cur[ks >> 1][r + 1], p.c, -m);
+        }
+        if (gu + 1 == n) {
+          xa[u] = fast_exp2(xa[u]);
+          xb[u] = fast_exp2(xb[u]);
+        }
+        if (gu + 2 == n) {
+          rs0 += xa[u];
+          rs1 += xb[u];
+          pt[e2] = pack_bf16(xa[u], xb[u]);
           if (e2 == 3) pb[ks] = __builtin_bit_cast(bf16x8, pt);
         }
-        if (n == NQ - 1) {
-          const float rs = sum_xor32(rs0 + rs1);
-          l += rs;
-          bs += rs;
-          if (SCORES && t % SPB == SPB - 1) {  // end of key block j0: log2 of the block's exp-sum
-            lval = m + fast_log2(bs);
-            bs = 0.f;
-          }
+      }
+      if (n == NQ + 2) {
+        const float rs = sum_xor32(rs0 + rs1);
+        l += rs;
+        bs += rs;
+        if (SCORES && t % SPB == SPB - 1) {  // end of key block j0: log2 of the block's exp-sum
+          lval = m + fast_log2(bs);
+          bs = 0.f;
         }
-      } else {
+      }
+      if (n >= NQ) {
         const int np = n - NQ;
         oacc[np % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], pb[np / DB], oacc[np % DB], 0, 0, 0);
-        // row max of S[t+1]: 16 max3 units spread over groups 2 .. NP-1-SP_MAXTAIL, then the running-max
-        // update SP_MAXTAIL groups before the end (its dependent chain hides under the last MFMAs)
+        // row max of S[t+1]: 16 max3 units spread over groups 2 .. NP-1-MAXTAIL, then the running-max
+        // update MAXTAIL groups before the end (its dependent chain hides under the last MFMAs)
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
-          if (2 + u * (NP - 2 - SP_MAXTAIL) / 16 != np) continue;
+          if (2 + u * (NP - 2 - MAXTAIL) / 16 != np) continue;
           const float a0 = s_next[u / 8][2 * (u % 8)], a1 = s_next[u / 8][2 * (u % 8) + 1];
           mx = (u == 0) ? fmaxf(a0, a1) : fmaxf(mx, fmaxf(a0, a1));
         }
-        if (np == NP - SP_MAXTAIL) {
+        if (np == NP - MAXTAIL) {
           mx = max_xor32(mx);
           const float m_new = lazy_max(m, mx * p.c);
           alpha = fast_exp2(m - m_new);
@@ -595,11 +494,8 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (SP_PRIO) __builtin_amdgcn_s_setprio(0);
-    TMARK(3);
     rescale(alpha);
     if (SCORES && t % SPB == SPB - 1 && h == 0) lrow[(int64_t)j0 * B] = lval;
-    TMARK(4);
   };
   // general step: per-wavefront causal mask / skip near the diagonal, optional next tile
   auto slow_step = [&](int t, int j0, int j1, int jv, int jk, f32x16(&s_cur)[2], f32x16(&s_next)[2]) {
@@ -623,14 +519,14 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
   };
 
   if (nsub > 0) {
-    // leading run of sub-tiles that lie before the first diagonal entry (of any wave group)
+    // leading run of sub-tiles that lie before the first diagonal entry of the list
     int nfast;
     if (DENSE) {
-      nfast = ((NG == 2) ? 2 * row : row) * SPB;
+      nfast = i * SPB;
     } else {
       int first = nblk;
       for (int e = lane; e < nblk; e += 64)
-        if (list[e] >= row) first = first < e ? first : e;
+        if (list[e] >= i) first = first < e ? first : e;
 #pragma unroll
       for (int off = 32; off >= 1; off >>= 1) {
         const int o2 = __shfl_xor(first, off, 64);
@@ -682,20 +578,12 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
       jw[5] = jn1;
     }
     wait_vm<0>();  // drain the ring's look-ahead loads before the LDS is reused or released
-#ifdef DIAG_TIMING
-    if (lane == 0 && p.dbg) {
-      unsigned long long *d = p.dbg + ((size_t)blockIdx.x * NWT + w) * 8;
-      for (int k = 0; k < 6; ++k) d[k] = tacc[k];
-      d[6] = nsub;
-      d[7] = nfast;
-    }
-#endif
   }
 
   // ---- output: O = O^T accumulators / l, rounded to bf16 ----
-  if (active) {
+  {
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
-    uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)ib * B + tq) * p.o_st + (int64_t)head * p.o_sh;
+    uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)i * B + tq) * p.o_st + (int64_t)head * p.o_sh;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -707,492 +595,25 @@ __global__ __launch_bounds__(B * 2 * NG, (B * NG) / 64 >= 2 ? 2 : 1) void attn_k
       }
   }
 
-  // ---- block-mass scores: S[ib][j] = (1/B) sum_t 2^(lws[j][t] - L_t), one row per wave group ----
+  // ---- block-mass scores: S[i][j] = (1/B) sum_t 2^(lws[j][t] - L_t) ----
   if (SCORES) {
-    float *lse_sh = reinterpret_cast<float *>(smem);  // [NG][B]; the rings are idle now
+    float *lse_sh = reinterpret_cast<float *>(smem);  // [B]; the rings are idle now
     __syncthreads();
-    if (active && h == 0) lse_sh[g * B + tq] = m + fast_log2(l);
+    if (h == 0) lse_sh[tq] = m + fast_log2(l);
     __threadfence();
     __syncthreads();
-    if (active) {
-      const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb) * B;
-      float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb;
-      for (int j = wg; j <= ib; j += NW) {
+    {
+      const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb) * B;
+      float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb;
+      for (int j = w; j <= i; j += NW) {
         float acc = 0.f;
 #pragma unroll
-        for (int t = lane; t < B; t += 64) acc += fast_exp2(lblk[(int64_t)j * B + t] - lse_sh[g * B + t]);
+        for (int t = lane; t < B; t += 64) acc += fast_exp2(lblk[(int64_t)j * B + t] - lse_sh[t]);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
         if (lane == 0) srow[j] = acc * (1.f / B);
       }
-      for (int j = ib + 1 + wg * 64 + lane; j < nkb; j += NW * 64) srow[j] = 0.f;
-    }
-  }
-}
-
-// MFMA issued from inline assembly, used by the wide kernel: it pins the register files (S tiles in
-// architectural VGPRs where the VALU reads them without copies; O and Q in accumulation VGPRs),
-// which the builtin form cannot do once a kernel uses more than 256 registers.  The compiler does not
-// see these as MFMAs, so the kernel keeps the required distance between an MFMA and any other
-// instruction that touches its result itself (mfma_drain before the VALU / memory code reads S or O).
-__device__ __forceinline__ void mfma_s0(f32x16 &acc, const bf16x8 &a, const bf16x8 &bq) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(bq));
-}
-__device__ __forceinline__ void mfma_s(f32x16 &acc, const bf16x8 &a, const bf16x8 &bq) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(bq));
-}
-__device__ __forceinline__ void mfma_o(f32x16 &acc, const bf16x8 &a, const bf16x8 &bp) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(bp));
-}
-// 80 idle issue cycles: every MFMA issued before it (two can still be queued) has written its result
-__device__ __forceinline__ void mfma_drain() {
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-}
-
-// ---------------------------------------------------------------------------------------------
-// attention kernel, wide variant (block = 128): 64 queries per wavefront, one wavefront per SIMD
-// ---------------------------------------------------------------------------------------------
-// Same pipeline as attn_kernel, but every wavefront owns two 32-query halves, so each K / V
-// fragment read from LDS and each byte brought through the vector L1 feeds two MFMAs.  A workgroup
-// is 4 wavefronts = 256 queries = two wave groups (two consecutive query blocks of one head, or one
-// query block of two heads that use the same list), one workgroup per CU, 4-deep K and V rings
-// (128 KiB of LDS at head_dim 128).  With half as many LDS / VMEM instructions per MFMA a single
-// wavefront keeps the matrix pipe busy on its own, which is what the 512-register budget buys.
-template <int D, bool DENSE, bool SCORES>
-__global__ __launch_bounds__(256, 1) void attn_wide_kernel(AttnParams p) {
-  constexpr int B = 128;
-  constexpr int NWT = 4;            // wavefronts per workgroup, 64 queries each
-  constexpr int SPB = B / KT;       // sub-tiles per key block
-  constexpr int IMG = KT * D * 2;   // bytes of a packed K (or V) image
-  constexpr int STAGE = 2 * IMG;
-  constexpr int DS = D / 16;
-  constexpr int DB = D / 32;
-  constexpr int DK = 4, DV = 3;
-  constexpr int RK = DK, RV = DV + 1;
-  constexpr int CH = IMG / 1024 / NWT;
-  constexpr int VM_KEEP = ((2 * DV - 1) < (2 * DK - 4) ? (2 * DV - 1) : (2 * DK - 4)) * CH;
-  __shared__ __attribute__((aligned(1024))) char smem[(RK + RV) * IMG];
-  const uint32_t lds_k = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
-  const uint32_t lds_v = lds_k + RK * IMG;
-
-  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, c32 = lane & 31;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int g = w >> 1, wg = w & 1;  // wave group, wavefront inside the group (64 queries each)
-  const int xcd = blockIdx.x & 7;
-  int rest = blockIdx.x >> 3;
-  const int slot = xcd * p.ncol + rest % p.ncol;
-  rest /= p.ncol;
-  const int row = p.nrows - 1 - (rest % p.nrows);
-  const int b = rest / p.nrows;
-  if (p.head_a[slot] < 0) return;
-  const int nkb = p.nqb;
-  const int head = (!DENSE && g == 1) ? p.head_b[slot] : p.head_a[slot];
-  const int ib = DENSE ? 2 * row + g : row;
-  const bool active = head >= 0 && ib < p.nqb;
-  const int hpos = p.pos_a[slot];
-  const int kvh = p.head_a[slot] / p.group;
-
-  int tq[2];  // this lane's two queries inside the block
-  tq[0] = 64 * wg + c32;
-  tq[1] = tq[0] + 32;
-  bf16x8 qf[2][DS];
-#pragma unroll
-  for (int qh = 0; qh < 2; ++qh) {
-    // Q fragments go straight into accumulation VGPRs and are defined by this statement alone (idle
-    // wave groups read a valid row too), so they stay there for the whole kernel; the wait sits in
-    // the same statement because the compiler treats the outputs as valid as soon as it ends.
-    const int head_ld = head >= 0 ? head : p.head_a[slot];
-    const int ib_ld = ib < p.nqb ? ib : p.nqb - 1;
-    const uint16_t *qp =
-        p.q + (int64_t)b * p.q_sb + ((int64_t)ib_ld * B + tq[qh]) * p.q_st + (int64_t)head_ld * p.q_sh + 8 * h;
-    if constexpr (DS == 8) {
-      asm volatile(
-          "global_load_dwordx4 %0, %8, off\n\tglobal_load_dwordx4 %1, %8, off offset:32\n\t"
-          "global_load_dwordx4 %2, %8, off offset:64\n\tglobal_load_dwordx4 %3, %8, off offset:96\n\t"
-          "global_load_dwordx4 %4, %8, off offset:128\n\tglobal_load_dwordx4 %5, %8, off offset:160\n\t"
-          "global_load_dwordx4 %6, %8, off offset:192\n\tglobal_load_dwordx4 %7, %8, off offset:224\n\t"
-          "s_waitcnt vmcnt(0)"
-          : "=&a"(qf[qh][0]), "=&a"(qf[qh][1]), "=&a"(qf[qh][2]), "=&a"(qf[qh][3]), "=&a"(qf[qh][4]),
-            "=&a"(qf[qh][5]), "=&a"(qf[qh][6]), "=&a"(qf[qh][7])
-          : "v"(qp)
-          : "memory");
-    } else {
-      asm volatile(
-          "global_load_dwordx4 %0, %4, off\n\tglobal_load_dwordx4 %1, %4, off offset:32\n\t"
-          "global_load_dwordx4 %2, %4, off offset:64\n\tglobal_load_dwordx4 %3, %4, off offset:96\n\t"
-          "s_waitcnt vmcnt(0)"
-          : "=&a"(qf[qh][0]), "=&a"(qf[qh][1]), "=&a"(qf[qh][2]), "=&a"(qf[qh][3])
-          : "v"(qp)
-          : "memory");
-    }
-  }
-  f32x16 oacc[2][DB];
-#pragma unroll
-  for (int qh = 0; qh < 2; ++qh)
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[qh][db][r] = 0.f;
-  float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f}, bs[2] = {0.f, 0.f};
-
-  int nblk;
-  const int32_t *list = nullptr;
-  if (DENSE) {
-    nblk = (2 * row + 1 < p.nqb) ? 2 * row + 2 : 2 * row + 1;
-  } else {
-    const int64_t lrow_id = ((int64_t)b * p.n_maps + p.head_map[slot]) * p.nqb + row;
-    nblk = p.kb_cnt[lrow_id];
-    nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
-    list = p.kb_idx + lrow_id * nkb;
-  }
-  const int nsub = nblk * SPB;
-  const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
-  float *lrow = nullptr;  // block-local log-sum-exp row of query tq[0]; tq[1] sits 32 floats further
-  if (SCORES) lrow = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb) * B + tq[0];
-
-  auto block_of = [&](int t) -> int {
-    int e = (t < nsub ? t : nsub - 1) / SPB;
-    if (DENSE) return e;
-    const int j = list[e];
-    return j < 0 ? 0 : (j > row ? row : j);
-  };
-  // what half qh of this wavefront has to do for sub-tile `sub` of key block j:
-  // 0 all of it, 1 causal mask, 2 nothing
-  auto mode_of = [&](int j, int sub, int qh) -> int {
-    if (!active || j > ib) return 2;
-    if (j != ib) return 0;
-    const int klo = KT * sub, qlo = 64 * wg + 32 * qh;
-    return (klo > qlo + 31) ? 2 : ((klo + KT - 1 <= qlo) ? 0 : 1);
-  };
-  auto img_src = [&](int t, int j, bool is_v) -> const char * {
-    const int tt = t < nsub ? t : nsub - 1;
-    return kvbase + (int64_t)(j * SPB + tt % SPB) * STAGE + (is_v ? IMG : 0) + (w * CH) * 1024;
-  };
-  auto issue_img = [&](int t, int j, bool is_v, uint32_t slot_base) {
-    const char *src = img_src(t, j, is_v);
-#pragma unroll
-    for (int n = 0; n < CH; ++n) lds_dma16(src + n * 1024, lane * 16, slot_base + (w * CH + n) * 1024);
-  };
-#ifdef DIAG_TIMING
-  unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
-  unsigned long long tmark = 0;
-#endif
-  auto sync_and_fill = [&](int t, int jv, int jk) {
-    TMARK(5);
-    wait_vm<VM_KEEP>();
-    TMARK(0);
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    TMARK(1);
-    issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
-    issue_img(t + DK, jk, false, lds_k + ((t + DK) % RK) * IMG);
-    TMARK(2);
-  };
-
-  // ---- building blocks of the general (near-diagonal) step, one 32-query half at a time ----
-  auto qk_half = [&](const char *kbuf, int qh, f32x16(&s)[2]) {
-    const char *kb = kbuf + lane * 16;
-#pragma unroll
-    for (int ds = 0; ds < DS; ++ds)
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kb + (rb * DS + ds) * 1024);
-        if (ds == 0) mfma_s0(s[rb], a, qf[qh][ds]);
-        else mfma_s(s[rb], a, qf[qh][ds]);
-      }
-    mfma_drain();
-  };
-  auto max_half = [&](f32x16(&s)[2], int qh, int mode, int sub) -> float {
-    if (mode == 1) {
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kk = KT * sub + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (kk > tq[qh]) s[rb][r] = -INFINITY;
-        }
-    }
-    float mx = fmaxf(s[0][0], s[0][1]);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int r = (rb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[rb][r], s[rb][r + 1]));
-    mx = max_xor32(mx);
-    const float m_new = lazy_max(m[qh], mx * p.c);
-    const float alpha = fast_exp2(m[qh] - m_new);
-    m[qh] = m_new;
-    l[qh] *= alpha;
-    bs[qh] *= alpha;
-    return alpha;
-  };
-  auto exp_half = [&](f32x16(&s)[2], int qh, bf16x8(&pb)[4]) {
-    float rs0 = 0.f, rs1 = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      u32x4 t;
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        const int r = 8 * (ks & 1) + 2 * e2;
-        const float p0 = fast_exp2(__builtin_fmaf(s[ks >> 1][r], p.c, -m[qh]));
-        const float p1 = fast_exp2(__builtin_fmaf(s[ks >> 1][r + 1], p.c, -m[qh]));
-        rs0 += p0;
-        rs1 += p1;
-        t[e2] = pack_bf16(p0, p1);
-      }
-      pb[ks] = __builtin_bit_cast(bf16x8, t);
-    }
-    const float rs = sum_xor32(rs0 + rs1);
-    l[qh] += rs;
-    bs[qh] += rs;
-  };
-  auto rescale_half = [&](int qh, float alpha) {
-    if (__any(alpha != 1.f)) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[qh][db][r] *= alpha;
-    }
-  };
-  auto pv_half = [&](const char *vbuf, int qh, const bf16x8(&pb)[4]) {
-    const char *vb = vbuf + lane * 16;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vb + (db * 4 + ks) * 1024);
-        mfma_o(oacc[qh][db], a, pb[ks]);
-      }
-    mfma_drain();
-  };
-
-  // fast step: tiles t and t+1 off the diagonal for every wavefront.  Hand-laid schedule of
-  // NM = NQ + NP groups, one MFMA each; an LDS fragment feeds two consecutive groups (both halves).
-  //   groups 0 .. NQ-1        S[t+1][qh] += K frag * Q frag[qh]
-  //   groups NQ .. NM-1       O[qh] += V frag * P[t][qh] frag
-  //   VALU, spread evenly:    exp / row-sum / bf16 pack of S[t] over groups 0 .. 3NM/4-1 (the PV groups
-  //                           of the first 32 keys only need the first half of P), then the row max
-  //                           of S[t+1] and the running-max update in the last quarter.
-  auto fast_step = [&](int t, int j0, int jv, int jk, f32x16(&s_cur)[2][2], f32x16(&s_next)[2][2]) {
-    sync_and_fill(t, jv, jk);
-    if (!active) return;
-    const char *kb = smem + ((t + 1) % RK) * IMG + lane * 16;
-    const char *vb = smem + (RK + t % RV) * IMG + lane * 16;
-    constexpr int NFQ = 2 * DS, NFP = 4 * DB, NF = NFQ + NFP;  // fragments: K then V
-    constexpr int NQ = 2 * NFQ, NM = 2 * NF, PF = SGB_PRE;      // groups
-    constexpr int NEXP = (3 * NM) / 4;                            // groups that carry exp units
-    auto frag = [&](int f) -> bf16x8 {
-      if (f < NFQ) return *reinterpret_cast<const bf16x8 *>(kb + ((f % 2) * DS + f / 2) * 1024);
-      const int fp = f - NFQ;
-      return *reinterpret_cast<const bf16x8 *>(vb + ((fp % DB) * 4 + fp / DB) * 1024);
-    };
-    bf16x8 fr[PF + 1];
-    bf16x8 pb[2][4];
-    u32x4 pt;
-    float rs0[2] = {0.f, 0.f}, rs1[2] = {0.f, 0.f}, mx[2] = {0.f, 0.f}, lval[2] = {0.f, 0.f};
-    float alpha[2] = {1.f, 1.f};
-#pragma unroll
-    for (int f = 0; f < PF; ++f) fr[f] = frag(f);
-    static_for<NM>([&](auto nc) {
-      constexpr int n = decltype(nc)::value;
-      constexpr int f = n / 2, qh = n % 2;
-      if constexpr (qh == 0 && f + PF < NF) fr[(f + PF) % (PF + 1)] = frag(f + PF);
-      if constexpr (n < NQ) {
-        constexpr int rb = f % 2, ds = f / 2;
-        if constexpr (f < 2) mfma_s0(s_next[qh][rb], fr[f % (PF + 1)], qf[qh][ds]);
-        else mfma_s(s_next[qh][rb], fr[f % (PF + 1)], qf[qh][ds]);
-      } else {
-        constexpr int fp = f - NFQ, ks = fp / DB, db = fp % DB;
-        mfma_o(oacc[qh][db], fr[f % (PF + 1)], pb[qh][ks]);
-      }
-      // exp units: u = 8 ks + 4 qh' + e2, two scores each, unit u rides in group u * NEXP / 32
-      constexpr int u_lo = (32 * n + NEXP - 1) / NEXP, u_hi = (32 * (n + 1) + NEXP - 1) / NEXP;
-      static_for<(u_hi < 32 ? u_hi : 32) - (u_lo < 32 ? u_lo : 32)>([&](auto uc) {
-        constexpr int u = u_lo + decltype(uc)::value;
-        constexpr int ks = u / 8, q2 = (u / 4) % 2, e2 = u % 4, r = 8 * (ks & 1) + 2 * e2;
-        const float p0 = fast_exp2(__builtin_fmaf(s_cur[q2][ks >> 1][r], p.c, -m[q2]));
-        const float p1 = fast_exp2(__builtin_fmaf(s_cur[q2][ks >> 1][r + 1], p.c, -m[q2]));
-        rs0[q2] += p0;
-        rs1[q2] += p1;
-        pt[e2] = pack_bf16(p0, p1);
-        if constexpr (e2 == 3) pb[q2][ks] = __builtin_bit_cast(bf16x8, pt);
-      });
-      if constexpr (n == NEXP - 1 || n == NEXP) {  // row sums of the finished P tile, one half per group
-        constexpr int q2 = n - (NEXP - 1);
-        const float rs = sum_xor32(rs0[q2] + rs1[q2]);
-        l[q2] += rs;
-        bs[q2] += rs;
-        if (SCORES && t % SPB == SPB - 1) {  // end of key block j0: log2 of the block's exp-sum
-          lval[q2] = m[q2] + fast_log2(bs[q2]);
-          bs[q2] = 0.f;
-        }
-      }
-      // row max of S[t+1]: 32 units (two scores each) over groups NEXP+1 .. NM-5, then one
-      // running-max update per half in groups NM-4 and NM-3
-      if constexpr (n > NEXP && n < NM - 4) {
-        constexpr int NMX = NM - 5 - NEXP;  // groups that carry max units
-        constexpr int nn = n - (NEXP + 1);
-        constexpr int v_lo = (32 * nn + NMX - 1) / NMX, v_hi = (32 * (nn + 1) + NMX - 1) / NMX;
-        static_for<(v_hi < 32 ? v_hi : 32) - (v_lo < 32 ? v_lo : 32)>([&](auto vc) {
-          constexpr int u = v_lo + decltype(vc)::value;
-          constexpr int q2 = u / 16, rb = (u / 8) % 2, r = 2 * (u % 8);
-          const float a0 = s_next[q2][rb][r], a1 = s_next[q2][rb][r + 1];
-          if constexpr (u % 16 == 0) mx[q2] = fmaxf(a0, a1);
-          else mx[q2] = fmaxf(mx[q2], fmaxf(a0, a1));
-        });
-      }
-      if constexpr (n == NM - 4 || n == NM - 3) {
-        constexpr int q2 = n - (NM - 4);
-        const float mq = max_xor32(mx[q2]);
-        const float m_new = lazy_max(m[q2], mq * p.c);
-        alpha[q2] = fast_exp2(m[q2] - m_new);
-        m[q2] = m_new;
-        l[q2] *= alpha[q2];
-        bs[q2] *= alpha[q2];
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    TMARK(3);
-    if (__any(alpha[0] != 1.f || alpha[1] != 1.f)) mfma_drain();  // O is about to be read by the VALU
-    rescale_half(0, alpha[0]);
-    rescale_half(1, alpha[1]);
-    if (SCORES && t % SPB == SPB - 1 && h == 0) {
-      lrow[(int64_t)j0 * B] = lval[0];
-      lrow[(int64_t)j0 * B + 32] = lval[1];
-    }
-    TMARK(4);
-  };
-  // general step: per-half causal mask / skip near the diagonal, optional next tile
-  auto slow_step = [&](int t, int j0, int j1, int jv, int jk, f32x16(&s_cur)[2][2], f32x16(&s_next)[2][2]) {
-    sync_and_fill(t, jv, jk);
-    const char *k_next = smem + ((t + 1) % RK) * IMG;
-    const char *v_cur = smem + (RK + t % RV) * IMG;
-    const int sub = t % SPB, sub1 = (t + 1) % SPB;
-#pragma unroll
-    for (int qh = 0; qh < 2; ++qh) {
-      const int mode0 = mode_of(j0, sub, qh);
-      const int mode1 = (t + 1 < nsub) ? mode_of(j1, sub1, qh) : 2;
-      if (mode1 != 2) qk_half(k_next, qh, s_next[qh]);
-      if (mode0 != 2) {
-        bf16x8 pb[4];
-        exp_half(s_cur[qh], qh, pb);
-        pv_half(v_cur, qh, pb);
-      }
-      if (SCORES && sub == SPB - 1 && mode_of(j0, 0, qh) != 2) {
-        if (h == 0) lrow[(int64_t)j0 * B + 32 * qh] = m[qh] + fast_log2(bs[qh]);
-        bs[qh] = 0.f;
-      }
-      if (mode1 != 2) rescale_half(qh, max_half(s_next[qh], qh, mode1, sub1));
-    }
-  };
-
-  if (nsub > 0) {
-    int nfast;
-    if (DENSE) {
-      nfast = 2 * row * SPB;
-    } else {
-      int first = nblk;
-      for (int e = lane; e < nblk; e += 64)
-        if (list[e] >= row) first = first < e ? first : e;
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) {
-        const int o2 = __shfl_xor(first, off, 64);
-        first = first < o2 ? first : o2;
-      }
-      nfast = __builtin_amdgcn_readfirstlane(first) * SPB;
-    }
-    nfast = nfast > 0 ? ((nfast - 1) & ~1) : 0;
-
-    f32x16 s_a[2][2], s_b[2][2];
-    int jw[6];
-#pragma unroll
-    for (int n = 0; n < 6; ++n) jw[n] = block_of(n);
-#pragma unroll
-    for (int n = 0; n < DK; ++n) {
-      if (n < DV && n < nsub) issue_img(n, jw[n], true, lds_v + (n % RV) * IMG);
-      if (n < nsub) issue_img(n, jw[n], false, lds_k + (n % RK) * IMG);
-    }
-    wait_vm<0>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-#pragma unroll
-    for (int qh = 0; qh < 2; ++qh) {
-      const int mode = mode_of(jw[0], 0, qh);
-      if (mode != 2) {
-        qk_half(smem, qh, s_a[qh]);
-        max_half(s_a[qh], qh, mode, 0);  // O is still zero: nothing to rescale
-      }
-    }
-    int t = 0;
-    for (; t < nfast; t += 2) {
-      const int jn0 = block_of(t + 6), jn1 = block_of(t + 7);
-      fast_step(t, jw[0], jw[DV], jw[DK], s_a, s_b);
-      fast_step(t + 1, jw[1], jw[DV + 1], jw[DK + 1], s_b, s_a);
-#pragma unroll
-      for (int n = 0; n < 4; ++n) jw[n] = jw[n + 2];
-      jw[4] = jn0;
-      jw[5] = jn1;
-    }
-    for (; t < nsub; t += 2) {
-      const int jn0 = block_of(t + 6), jn1 = block_of(t + 7);
-      slow_step(t, jw[0], jw[1], jw[DV], jw[DK], s_a, s_b);
-      if (t + 1 < nsub) slow_step(t + 1, jw[1], jw[2], jw[DV + 1], jw[DK + 1], s_b, s_a);
-#pragma unroll
-      for (int n = 0; n < 4; ++n) jw[n] = jw[n + 2];
-      jw[4] = jn0;
-      jw[5] = jn1;
-    }
-    wait_vm<0>();  // drain the ring's look-ahead loads before the LDS is reused or released
-#ifdef DIAG_TIMING
-    if (lane == 0 && p.dbg) {
-      unsigned long long *d = p.dbg + ((size_t)blockIdx.x * NWT + w) * 8;
-      for (int k = 0; k < 6; ++k) d[k] = tacc[k];
-      d[6] = nsub;
-      d[7] = nfast;
-    }
-#endif
-  }
-
-  // ---- output: O = O^T accumulators / l, rounded to bf16 ----
-  mfma_drain();
-  if (active) {
-#pragma unroll
-    for (int qh = 0; qh < 2; ++qh) {
-      const float inv = (l[qh] > 0.f) ? 1.f / l[qh] : 0.f;
-      uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)ib * B + tq[qh]) * p.o_st + (int64_t)head * p.o_sh;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          u32x2 tt;
-          tt[0] = pack_bf16(oacc[qh][db][4 * gq] * inv, oacc[qh][db][4 * gq + 1] * inv);
-          tt[1] = pack_bf16(oacc[qh][db][4 * gq + 2] * inv, oacc[qh][db][4 * gq + 3] * inv);
-          *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * gq + 4 * h) = tt;
-        }
-    }
-  }
-
-  // ---- block-mass scores: S[ib][j] = (1/B) sum_t 2^(lws[j][t] - L_t), one row per wave group ----
-  if (SCORES) {
-    float *lse_sh = reinterpret_cast<float *>(smem);  // [2][B]; the rings are idle now
-    __syncthreads();
-    if (active && h == 0) {
-      lse_sh[g * B + tq[0]] = m[0] + fast_log2(l[0]);
-      lse_sh[g * B + tq[1]] = m[1] + fast_log2(l[1]);
-    }
-    __threadfence();
-    __syncthreads();
-    if (active) {
-      const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb) * B;
-      float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + ib) * nkb;
-      for (int j = wg; j <= ib; j += 2) {
-        float acc = 0.f;
-#pragma unroll
-        for (int t = lane; t < B; t += 64) acc += fast_exp2(lblk[(int64_t)j * B + t] - lse_sh[g * B + t]);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-        if (lane == 0) srow[j] = acc * (1.f / B);
-      }
-      for (int j = ib + 1 + wg * 64 + lane; j < nkb; j += 2 * 64) srow[j] = 0.f;
+      for (int j = i + 1 + w * 64 + lane; j < nkb; j += NW * 64) srow[j] = 0.f;
     }
   }
 }
@@ -1444,9 +865,6 @@ void fill_attn(AttnParams &ap, const sp_shape *s, const void *q, const void *kvp
   ap.group = s->n_q_heads / s->n_kv_heads;
   const float scale = (s->softmax_scale > 0.f) ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
   ap.c = scale * 1.4426950408889634f;
-#ifdef DIAG_TIMING
-  ap.dbg = g_dbg_ptr();
-#endif
 }
 
 // Host-side view of one attention launch: the listed heads in the caller's order.
@@ -1458,12 +876,9 @@ struct HeadList {
 
 // Builds the slot table and launches.  The listed heads are sorted by (kv head, list, head) and
 // dealt to the 8 XCDs in contiguous runs of `ncol` slots, so heads that read the same K/V images
-// (and, for the sparse kernel, walk the same list) run on one XCD together.
-//   dense : one slot per head; with TWO_GROUPS a workgroup takes two consecutive query blocks
-//   sparse: with TWO_GROUPS a slot is a pair of heads with the same (kv head, list); a head left
-//           over runs alone in its slot (second wave group idle)
-template <bool DENSE, int NG, bool WIDE>
-sp_status launch_attn_ng(const sp_shape *s, AttnParams ap, const HeadList &hl, hipStream_t st) {
+// (and, for the sparse kernel, walk the same list) run on one XCD together and meet in its L2.
+template <bool DENSE>
+sp_status launch_attn(const sp_shape *s, AttnParams ap, const HeadList &hl, hipStream_t st) {
   const int n = hl.n;
   struct Ent {
     int kvh, map, head, pos;
@@ -1474,29 +889,14 @@ sp_status launch_attn_ng(const sp_shape *s, AttnParams ap, const HeadList &hl, h
     if (x.map != y.map) return x.map < y.map;
     return x.head < y.head;
   });
-  struct Slot {
-    int a, b, map, pos;
-  } slots[SP_MAX_HEADS];
-  int ns = 0;
-  for (int a = 0; a < n;) {
-    if (!DENSE && NG == 2 && a + 1 < n && ent[a + 1].kvh == ent[a].kvh && ent[a + 1].map == ent[a].map) {
-      slots[ns++] = {ent[a].head, ent[a + 1].head, ent[a].map, ent[a].pos};
-      a += 2;
-    } else {
-      slots[ns++] = {ent[a].head, -1, ent[a].map, ent[a].pos};
-      a += 1;
-    }
-  }
   ap.n_heads = n;
-  ap.ncol = (ns + 7) / 8;
-  ap.nrows = (DENSE && NG == 2) ? (ap.nqb + 1) / 2 : ap.nqb;
+  ap.ncol = (n + 7) / 8;
   for (int a = 0; a < 8 * ap.ncol; ++a) {
-    ap.head_a[a] = a < ns ? slots[a].a : -1;
-    ap.head_b[a] = a < ns ? slots[a].b : -1;
-    ap.head_map[a] = a < ns ? slots[a].map : 0;
-    ap.pos_a[a] = a < ns ? slots[a].pos : 0;
+    ap.head_ids[a] = a < n ? ent[a].head : -1;
+    ap.head_map[a] = a < n ? ent[a].map : 0;
+    ap.head_pos[a] = a < n ? ent[a].pos : 0;
   }
-  const int64_t nwg = (int64_t)s->batch * 8 * ap.ncol * ap.nrows;
+  const int64_t nwg = (int64_t)s->batch * 8 * ap.ncol * ap.nqb;
   if (nwg <= 0 || nwg > 0x7FFFFFFF) {
     set_err("grid too large");
     return SP_ERR_UNSUPPORTED;
@@ -1504,26 +904,14 @@ sp_status launch_attn_ng(const sp_shape *s, AttnParams ap, const HeadList &hl, h
   dim3 grid((unsigned)nwg);
   const bool sc = DENSE && ap.scores != nullptr;
   ProfScope prof(DENSE ? KK_DENSE : KK_SPARSE, st);
-#define SP_LAUNCH(D_, B_)                                                                                   \
-  do {                                                                                                      \
-    if (sc)                                                                                                 \
-      hipLaunchKernelGGL((attn_kernel<D_, B_, NG, true, true>), grid, dim3(B_ * 2 * NG), 0, st, ap);       \
-    else                                                                                                    \
-      hipLaunchKernelGGL((attn_kernel<D_, B_, NG, DENSE, false>), grid, dim3(B_ * 2 * NG), 0, st, ap);     \
+#define SP_LAUNCH(D_, B_)                                                                           \
+  do {                                                                                              \
+    if (sc)                                                                                         \
+      hipLaunchKernelGGL((attn_kernel<D_, B_, true, true>), grid, dim3(B_ * 2), 0, st, ap);        \
+    else                                                                                            \
+      hipLaunchKernelGGL((attn_kernel<D_, B_, DENSE, false>), grid, dim3(B_ * 2), 0, st, ap);      \
   } while (0)
-#define SP_LAUNCH_WIDE(D_)                                                                   \
-  do {                                                                                       \
-    if (sc)                                                                                  \
-      hipLaunchKernelGGL((attn_wide_kernel<D_, true, true>), grid, dim3(256), 0, st, ap);   \
-    else                                                                                     \
-      hipLaunchKernelGGL((attn_wide_kernel<D_, DENSE, false>), grid, dim3(256), 0, st, ap); \
-  } while (0)
-  if (WIDE && s->block == 128) {
-    if (s->head_dim == 128)
-      SP_LAUNCH_WIDE(128);
-    else
-      SP_LAUNCH_WIDE(64);
-  } else if (s->head_dim == 128 && s->block == 128)
+  if (s->head_dim == 128 && s->block == 128)
     SP_LAUNCH(128, 128);
   else if (s->head_dim == 128 && s->block == 64)
     SP_LAUNCH(128, 64);
@@ -1532,23 +920,7 @@ sp_status launch_attn_ng(const sp_shape *s, AttnParams ap, const HeadList &hl, h
   else
     SP_LAUNCH(64, 64);
 #undef SP_LAUNCH
-#undef SP_LAUNCH_WIDE
   return hip_check(hipGetLastError(), DENSE ? "dense attn_kernel launch" : "sparse attn_kernel launch");
-}
-
-#ifndef SP_DENSE_WIDE
-#define SP_DENSE_WIDE 0
-#endif
-#ifndef SP_SPARSE_WIDE
-#define SP_SPARSE_WIDE 0
-#endif
-// block 128: the wide kernel (two wave groups per workgroup, 64 queries per wavefront);
-// block 64: the narrow kernel, one query block per workgroup
-template <bool DENSE>
-sp_status launch_attn(const sp_shape *s, const AttnParams &ap, const HeadList &hl, hipStream_t st) {
-  constexpr bool kWide = DENSE ? (SP_DENSE_WIDE != 0) : (SP_SPARSE_WIDE != 0);
-  if (kWide && s->block == 128) return launch_attn_ng<DENSE, 2, true>(s, ap, hl, st);
-  return launch_attn_ng<DENSE, 1, false>(s, ap, hl, st);
 }
 
 sp_status launch_mask(const float *scores, int n_maps, int nqb, int nkb, float gamma, int32_t *kb_idx,
@@ -1600,9 +972,6 @@ const char *sp_status_string(sp_status s) {
 
 const char *sp_last_error(void) { return g_err; }
 
-#ifdef DIAG_TIMING
-void sp_debug_set_buffer(void *p) { g_dbg_store = (unsigned long long *)p; }
-#endif
 
 sp_status sp_profile_enable(int32_t on) {
   g_prof_on = on != 0;
