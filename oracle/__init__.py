@@ -12,6 +12,10 @@ Stages (one attention head at a time, arrays are float32 ``[N][d]``):
 * ``build_mask_rows`` Alg. 2 per query-block row in exact fixed point, plus the
                       forced sink and diagonal blocks
 * ``masked_rows``     Sec. 5.1 A(Q,K,V,M) over the listed key blocks
+* ``mean_logit_rows`` block-wise average of the scaled QK logits (Sec. 5.2, "Sparse
+                      Attention Computation"), ``softmax_rows`` Alg. 2's first step,
+                      ``build_mask_global`` Alg. 2 over the flattened map: the pattern
+                      construction as the paper prints it
 * ``prefill_layer``   Alg. 1 / Alg. 4 for one layer with given pivots: pivots run
                       dense, their score map becomes the cluster's pattern, all
                       other heads of the cluster run masked attention with it.
@@ -55,6 +59,14 @@ def _load():
         L.spo_masked_rows.restype = ctypes.c_int
         L.spo_masked_rows.argtypes = [fp, fp, fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                       ip, ctypes.c_int, ip, ip, fp]
+        L.spo_mean_logit_rows.restype = ctypes.c_int
+        L.spo_mean_logit_rows.argtypes = [fp, fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                          ip, ctypes.c_int, fp]
+        L.spo_softmax_rows.restype = ctypes.c_int
+        L.spo_softmax_rows.argtypes = [fp, ctypes.c_int, ctypes.c_int, fp]
+        L.spo_build_mask_global.restype = ctypes.c_int
+        L.spo_build_mask_global.argtypes = [fp, ctypes.c_int, ctypes.c_float, ctypes.c_int, ip, ip,
+                                            ctypes.POINTER(ctypes.c_int64)]
         _lib = L
     return _lib
 
@@ -151,9 +163,52 @@ def masked_rows(q, k, v, block: int, kb_idx, kb_cnt, rows: Optional[Sequence[int
     return o
 
 
+def mean_logit_rows(q, k, block: int, rows: Optional[Sequence[int]] = None, scale: Optional[float] = None):
+    """Block-wise average of the scaled causal logits of one head, [nrows][nkb], -inf beyond the diagonal."""
+    q, qp = _f(q)
+    k, kp = _f(k)
+    N, d = q.shape
+    nkb = N // block
+    rows = _rows(rows, nkb)
+    scale = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    out = np.empty((len(rows), nkb), dtype=np.float32)
+    rc = _load().spo_mean_logit_rows(qp, kp, N, d, block, scale,
+                                     rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(rows),
+                                     out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if rc:
+        raise ValueError(f"spo_mean_logit_rows failed ({rc})")
+    return out
+
+
+def softmax_rows(a):
+    """Row softmax (fp64 inside); -inf entries become exactly 0."""
+    a, ap = _f(a)
+    out = np.empty_like(a)
+    rc = _load().spo_softmax_rows(ap, a.shape[0], a.shape[1], out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if rc:
+        raise ValueError(f"spo_softmax_rows failed ({rc})")
+    return out
+
+
+def build_mask_global(scores, gamma: float, forced: bool = True):
+    """Alg. 2 over the whole (square, causal) score map.  Returns (kb_idx, kb_cnt, K)."""
+    scores, sp = _f(scores)
+    nkb = scores.shape[0]
+    assert scores.shape == (nkb, nkb)
+    idx = np.empty((nkb, nkb), dtype=np.int32)
+    cnt = np.empty((nkb,), dtype=np.int32)
+    K = ctypes.c_int64(0)
+    ip = ctypes.POINTER(ctypes.c_int32)
+    rc = _load().spo_build_mask_global(sp, nkb, ctypes.c_float(np.float32(gamma)), int(bool(forced)),
+                                       idx.ctypes.data_as(ip), cnt.ctypes.data_as(ip), ctypes.byref(K))
+    if rc:
+        raise ValueError(f"spo_build_mask_global failed ({rc})")
+    return idx, cnt, int(K.value)
+
+
 def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: float,
                   rows: Optional[Sequence[int]] = None, scale: Optional[float] = None,
-                  masks=None):
+                  masks=None, paper_pattern: bool = False):
     """One layer of pattern sharing with given pivots (Alg. 1 / Alg. 2 / Alg. 4).
 
     q [N][Hq][d], k/v [N][Hkv][d] float32.  Returns a dict with
@@ -162,7 +217,10 @@ def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: floa
       kb_idx  [C][nrows][nkb], kb_cnt [C][nrows]
     Heads with cluster id -1 run dense.  `masks`, if given as (kb_idx, kb_cnt) with
     those shapes, replaces the oracle's own pattern for the non-pivot heads (used
-    to check outputs against a pattern produced elsewhere)."""
+    to check outputs against a pattern produced elsewhere).  `paper_pattern` swaps
+    the pattern construction for the paper's printed one (row softmax of block-mean
+    logits, one selection over the flattened map, forced sink/diagonal kept); it
+    needs every row unless `masks` is given."""
     q = np.asarray(q, dtype=np.float32)
     k = np.asarray(k, dtype=np.float32)
     v = np.asarray(v, dtype=np.float32)
@@ -181,10 +239,17 @@ def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: floa
         p = int(p)
         assert int(head_to_cluster[p]) == c
         g = p // G
-        op, sc, _ = dense_rows(q[:, p], k[:, g], v[:, g], block, rows, scale)
+        op, sc, _ = dense_rows(q[:, p], k[:, g], v[:, g], block, rows, scale, want_scores=not paper_pattern)
         o[:, p] = op
-        scores[c] = sc
-        kb_idx[c], kb_cnt[c], _ = build_mask_rows(sc, gamma, rows)
+        if paper_pattern:
+            sc = softmax_rows(mean_logit_rows(q[:, p], k[:, g], block, rows, scale))
+            scores[c] = sc
+            if masks is None:
+                assert nr == nkb and np.array_equal(rows, np.arange(nkb)), "global selection needs the whole map"
+                kb_idx[c], kb_cnt[c], _ = build_mask_global(sc, gamma, forced=True)
+        else:
+            scores[c] = sc
+            kb_idx[c], kb_cnt[c], _ = build_mask_rows(sc, gamma, rows)
     if masks is not None:
         kb_idx, kb_cnt = masks
     pivots = {int(p) for p in pivot_heads}

@@ -27,6 +27,10 @@
  *
  * All functions take a list of query-block rows so that long sequences can be
  * checked on a sample of rows: row i only needs Q block i and K/V[0 .. (i+1)B).
+ *
+ * The second half of the file holds the pattern construction exactly as the
+ * paper prints it (block-mean logits, row softmax, one selection over the
+ * flattened map); see the comment there.
  */
 #include <math.h>
 #include <stdint.h>
@@ -276,4 +280,149 @@ int spo_masked_rows(const float *q, const float *k, const float *v, int N, int d
     free(on);
   }
   return fail ? 2 : 0;
+}
+
+/* ==== paper-literal pattern construction (Sec. 5.2, Alg. 2 as printed) ======
+ *
+ *   mean logits  Abar[i][j] = average of the scaled logits x[t][s] over the
+ *                entries of block (i, j) that exist (s <= t): B*B entries for
+ *                j < i, B(B+1)/2 on the diagonal block, none for j > i, which
+ *                gets -inf ("blocks not computed are assigned -inf").
+ *                (Sec. 5.2 "Sparse Attention Computation": block-wise average
+ *                of the QK values.)
+ *   row softmax  Atil[i][.] = softmax(Abar[i][.])        (Alg. 2, first step)
+ *   selection    the whole map is normalised by its total, flattened row-major,
+ *                sorted descending, and the shortest prefix whose sum reaches
+ *                gamma is kept (Alg. 2, remaining steps).  Ties: lower flat
+ *                index first.  Evaluated in exact 24-bit fixed point like the
+ *                per-row variant above.
+ */
+
+int spo_mean_logit_rows(const float *q, const float *k, int N, int d, int B, double scale, const int *rows,
+                        int nrows, float *abar) {
+  if (N <= 0 || d <= 0 || B <= 0 || N % B) return 1;
+  const int nkb = N / B;
+  for (int r = 0; r < nrows; ++r)
+    if (rows[r] < 0 || rows[r] >= nkb) return 1;
+  int fail = 0;
+#pragma omp parallel
+  {
+    double *x = (double *)malloc(sizeof(double) * (size_t)N);
+    double *sum = (double *)malloc(sizeof(double) * (size_t)nkb);
+    long *num = (long *)malloc(sizeof(long) * (size_t)nkb);
+    if (!x || !sum || !num) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int r = 0; r < nrows; ++r) {
+        const int i = rows[r];
+        for (int j = 0; j < nkb; ++j) {
+          sum[j] = 0.0;
+          num[j] = 0;
+        }
+        for (int tt = 0; tt < B; ++tt) {
+          const int t = i * B + tt;
+          logits_row(q, k, t, d, scale, x);
+          for (int s = 0; s <= t; ++s) {
+            sum[s / B] += x[s];
+            num[s / B] += 1;
+          }
+        }
+        for (int j = 0; j < nkb; ++j)
+          abar[(size_t)r * nkb + j] = (num[j] > 0) ? (float)(sum[j] / (double)num[j]) : -INFINITY;
+      }
+    }
+    free(x);
+    free(sum);
+    free(num);
+  }
+  return fail ? 2 : 0;
+}
+
+/* softmax of each row; -inf entries get exactly 0; a row of only -inf becomes all 0 */
+int spo_softmax_rows(const float *a, int nrows, int n, float *out) {
+  if (nrows < 0 || n <= 0) return 1;
+  for (int r = 0; r < nrows; ++r) {
+    const float *row = a + (size_t)r * n;
+    double mx = -INFINITY;
+    for (int j = 0; j < n; ++j)
+      if ((double)row[j] > mx) mx = row[j];
+    double den = 0.0;
+    if (mx > -INFINITY)
+      for (int j = 0; j < n; ++j) den += exp((double)row[j] - mx);
+    for (int j = 0; j < n; ++j)
+      out[(size_t)r * n + j] = (den > 0.0) ? (float)(exp((double)row[j] - mx) / den) : 0.0f;
+  }
+  return 0;
+}
+
+typedef struct {
+  uint32_t u;
+  int64_t f; /* flat index i * nkb + j */
+} spo_gkey;
+
+static int gkey_cmp(const void *a, const void *b) {
+  const spo_gkey *x = (const spo_gkey *)a, *y = (const spo_gkey *)b;
+  if (x->u != y->u) return (x->u > y->u) ? -1 : 1;
+  return (x->f < y->f) ? -1 : (x->f > y->f);
+}
+
+/*
+ * Alg. 2 on the whole map.  scores [nkb][nkb] (row i = query block i; entries
+ * with j > i are ignored: they do not exist under causality).
+ *   forced   nonzero: every row additionally receives the sink block 0 and its
+ *            diagonal block (not in the paper; keeps every query row non-empty)
+ *   kb_idx   [nkb][nkb] ascending, -1 tail;  kb_cnt [nkb]
+ *   k_star   (may be NULL) the global K before forced blocks
+ */
+int spo_build_mask_global(const float *scores, int nkb, float gamma, int forced, int32_t *kb_idx,
+                          int32_t *kb_cnt, int64_t *k_star) {
+  if (nkb <= 0 || nkb > 32768 || !(gamma > 0.0f) || gamma > 1.0f) return 1;
+  const uint64_t gq = (uint64_t)rintf(gamma * 16777216.0f);
+  const size_t n = (size_t)nkb * ((size_t)nkb + 1) / 2;
+  spo_gkey *keys = (spo_gkey *)malloc(sizeof(spo_gkey) * n);
+  unsigned char *on = (unsigned char *)calloc((size_t)nkb * (size_t)nkb, 1);
+  if (!keys || !on) {
+    free(keys);
+    free(on);
+    return 2;
+  }
+  size_t m = 0;
+  unsigned __int128 tot = 0;
+  for (int i = 0; i < nkb; ++i)
+    for (int j = 0; j <= i; ++j) {
+      keys[m].u = quantise(scores[(size_t)i * nkb + j]);
+      keys[m].f = (int64_t)i * nkb + j;
+      tot += keys[m].u;
+      ++m;
+    }
+  qsort(keys, n, sizeof(spo_gkey), gkey_cmp);
+  int64_t K = 0;
+  if (tot > 0) {
+    unsigned __int128 cum = 0;
+    for (size_t kk = 0; kk < n; ++kk) {
+      cum += keys[kk].u;
+      if ((cum << 24) >= (unsigned __int128)gq * tot) { /* cum / tot >= gamma, exactly */
+        K = (int64_t)kk + 1;
+        break;
+      }
+    }
+  }
+  for (int64_t kk = 0; kk < K; ++kk) on[keys[kk].f] = 1;
+  for (int i = 0; i < nkb; ++i) {
+    if (forced) {
+      on[(size_t)i * nkb] = 1;
+      on[(size_t)i * nkb + i] = 1;
+    }
+    int c = 0;
+    for (int j = 0; j < nkb; ++j)
+      if (j <= i && on[(size_t)i * nkb + j]) kb_idx[(size_t)i * nkb + c++] = j;
+    kb_cnt[i] = c;
+    for (; c < nkb; ++c) kb_idx[(size_t)i * nkb + c] = -1;
+  }
+  if (k_star) *k_star = K;
+  free(keys);
+  free(on);
+  return 0;
 }
