@@ -42,6 +42,10 @@ def main() -> int:
     ap.add_argument("--config", default="llama8b_128k")
     ap.add_argument("--seq", type=int, default=None, help="override the sequence length (debug)")
     ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--score-mode", choices=["mass", "mean-logit"], default="mass",
+                    help="pivot score map: exact block mass (default) or the paper's row softmax of block-mean logits")
+    ap.add_argument("--select-mode", choices=["row", "global"], default="row",
+                    help="Alg. 2 per query-block row (default) or once over the flattened map as printed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-all", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -75,8 +79,16 @@ def main() -> int:
     kb_idx = torch.empty((1, C, nqb, nqb), dtype=torch.int32, device="cuda")
     kb_cnt = torch.empty((1, C, nqb), dtype=torch.int32, device="cuda")
 
+    score_mode = sp.SP_SCORE_MEAN_LOGIT if args.score_mode == "mean-logit" else sp.SP_SCORE_BLOCK_MASS
+    select_mode = sp.SP_SELECT_GLOBAL if args.select_mode == "global" else sp.SP_SELECT_PER_ROW
+    default_modes = args.score_mode == "mass" and args.select_mode == "row"
+
     def step():
-        sp.sp_prefill_layer(shape, q, k, v, h2c, piv, cfg.gamma, o, scores, kb_idx, kb_cnt, ws)
+        if default_modes:
+            sp.sp_prefill_layer(shape, q, k, v, h2c, piv, cfg.gamma, o, scores, kb_idx, kb_cnt, ws)
+        else:
+            sp.sp_prefill_layer_modes(shape, q, k, v, h2c, piv, cfg.gamma, score_mode, select_mode, o, scores,
+                                      kb_idx, kb_cnt, ws)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
@@ -89,11 +101,15 @@ def main() -> int:
     torch.cuda.synchronize()
     sp.sp_profile_enable(True)
     sp.sp_profile_read(reset=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # same stream as the launches
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for n in range(args.steps):
         step()
+        marks[n + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    per_step = sorted(marks[n].elapsed_time(marks[n + 1]) for n in range(args.steps))
     prof = sp.sp_profile_read(reset=True)
     sp.sp_profile_enable(False)
     ms_step = wall * 1e3 / args.steps
@@ -148,6 +164,8 @@ def main() -> int:
                                f"1 pivot each, gamma {cfg.gamma}",
                    "seed": L["seed"], "density": density},
         "ms_per_layer": ms_step,
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "pattern": {"score_mode": args.score_mode, "select_mode": args.select_mode},
         "computed_tflops": computed_flops / (ms_step * 1e-3) / 1e12,
         "computed_frac_of_bf16_peak": computed_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "tiles": {"pivot": int(pivot_tiles), "sparse": int(sparse_tiles),
@@ -165,6 +183,12 @@ def main() -> int:
                      "launch_ms": dense_avg_ms},
         "input_gen_s": gen_s,
     }
+    # the published peak next to what this board's CU count and maximum engine clock give
+    props = torch.cuda.get_device_properties(0)
+    out["roofline"]["peak_source"] = "published MI355X dense bf16 MFMA figure (256 CUs x 4096 flop/clk x 2.4 GHz)"
+    out["roofline"]["board"] = {"name": props.name, "cus": props.multi_processor_count,
+                                "max_engine_clock_mhz": props.clock_rate / 1e3,
+                                "derived_peak_tflops": props.multi_processor_count * 4096 * props.clock_rate * 1e3 / 1e12}
 
     if not args.no_cpu_baseline:
         import oracle

@@ -62,19 +62,28 @@ const char *sp_last_error(void);
  * App. A.2 "Latency Benchmark", times whole runs).  While enabled, every kernel the calls
  * below launch is bracketed by two HIP events on the caller's stream.  After the caller has
  * synchronised that stream, sp_profile_read sums elapsed milliseconds and launch counts per
- * kernel kind into host arrays ms[4] / launches[4]: 0 = K/V packing, 1 = dense attention
- * (+ scores), 2 = mask builder, 3 = block-sparse attention; `reset` != 0 drops the records.
+ * kernel kind into host arrays ms[5] / launches[5]: 0 = K/V packing, 1 = dense attention
+ * (+ block-mass scores), 2 = mask builder, 3 = block-sparse attention, 4 = block-mean-logit
+ * scores; `reset` != 0 drops the records.
  * Process-wide and not thread-safe.
  */
 sp_status sp_profile_enable(int32_t on);
 sp_status sp_profile_read(float *ms, int32_t *launches, int32_t reset);
 
 /*
- * Bytes of device workspace needed by the calls below for this shape when at most
- * `n_dense_heads` heads per batch entry run dense attention *with* block scores in
- * one call (0 if no scores are ever requested).
+ * Bytes of device workspace that suffice for any of the attention calls below
+ * (sp_dense_attn_with_block_scores, sp_block_sparse_attn, sp_prefill_layer,
+ * sp_prefill_layer_modes in every mode) for this shape when at most `n_dense_heads`
+ * heads per batch entry produce a block score map in one call (0 if no scores are
+ * ever requested).
  */
 sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_t *bytes);
+
+/* Workspace of sp_block_mean_logit_scores for n_heads listed heads. */
+sp_status sp_score_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *bytes);
+
+/* Workspace of sp_build_block_mask_global for n_maps maps of nqb x nqb blocks. */
+sp_status sp_mask_workspace_bytes(int32_t n_maps, int32_t nqb, size_t *bytes);
 
 /*
  * Dense causal attention A(Q,K,V) (Sec. 5.1) for the listed query heads, and the
@@ -124,6 +133,48 @@ sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void 
                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The block score map as the paper prints it (Sec. 5.2, "Sparse Attention Computation"
+ * and the first step of Alg. 2) for the listed heads: Abar[i][j] = the average of the
+ * scaled logits q_t.k_s*scale over the entries of block (i,j) that exist under
+ * causality (all block*block of them for j < i, the block(block+1)/2 with s <= t on
+ * the diagonal, -inf for j > i), then a softmax over each row i.  Every row of the
+ * result sums to 1; entries with j > i are 0.  No attention output is produced: the
+ * averages are linear in Q and K and are formed from per-block sums.
+ *   q, k         device bf16 (shape's strides; V is not read)
+ *   head_ids     host [n_heads] distinct query-head ids
+ *   block_scores device fp32 [batch][n_heads][nqb][nkb]   (output)
+ *   workspace    sp_score_workspace_bytes(shape, n_heads)
+ * Row nqb-1 of a head's map is the representative vector a~ that Alg. 2 stores.
+ */
+sp_status sp_block_mean_logit_scores(const sp_shape *shape, const void *q, const void *k, const int32_t *head_ids,
+                                     int32_t n_heads, float *block_scores, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+
+/*
+ * Alg. 2 (Construct Pivotal Pattern) as printed, one selection per map: the causal
+ * entries (j <= i) of a map are quantised as in sp_build_block_mask, normalised by the
+ * map's total, flattened row-major and ordered by (u descending, flat index ascending);
+ * K = the least k >= 1 whose prefix sum times 2^24 reaches rint(gamma * 2^24) * total
+ * (K = 0 for an all-zero map); entry (i, j) of that prefix puts key block j into row i's
+ * list.  `forced` != 0 additionally gives every row its sink block 0 and diagonal block i
+ * (not in the paper; without it a row's list may be empty and that query block then
+ * attends to nothing).
+ *   block_scores device fp32 [n_maps][nqb][nkb]  (nqb == nkb required; n_maps <= 65535)
+ *   kb_idx       device int32 [n_maps][nqb][nkb] ascending key blocks, tail = -1
+ *   kb_cnt       device int32 [n_maps][nqb]
+ *   workspace    sp_mask_workspace_bytes(n_maps, nqb); contents are scratch
+ */
+sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb, float gamma,
+                                     int32_t forced, int32_t *kb_idx, int32_t *kb_cnt, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream);
+
+/* How the pivot's block score map is formed / how Alg. 2 turns it into a pattern. */
+enum { SP_SCORE_BLOCK_MASS = 0,   /* exact attention mass per block (sp_dense_attn_with_block_scores) */
+       SP_SCORE_MEAN_LOGIT = 1 }; /* row softmax of block-mean logits (sp_block_mean_logit_scores) */
+enum { SP_SELECT_PER_ROW = 0,     /* sp_build_block_mask */
+       SP_SELECT_GLOBAL = 1 };    /* sp_build_block_mask_global with forced = 1 */
+
+/*
  * One layer of pattern sharing (Alg. 1 with the pattern source of Alg. 4 and the
  * pattern construction of Alg. 2): pivot heads run dense attention with block
  * scores, each cluster's score map becomes its key-block lists, and every other
@@ -139,6 +190,18 @@ sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, 
                            const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
                            float gamma, void *o, float *block_scores, int32_t *kb_idx, int32_t *kb_cnt,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * sp_prefill_layer with the pattern construction selectable: score_mode / select_mode =
+ * (SP_SCORE_MEAN_LOGIT, SP_SELECT_GLOBAL) is Alg. 2 as the paper prints it (Sec. 5.2),
+ * (SP_SCORE_BLOCK_MASS, SP_SELECT_PER_ROW) is sp_prefill_layer; the other two mix them.
+ * All other arguments, outputs and errors as for sp_prefill_layer.
+ */
+sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                 const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                                 float gamma, int32_t score_mode, int32_t select_mode, void *o, float *block_scores,
+                                 int32_t *kb_idx, int32_t *kb_cnt, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,12 @@ EXPORTED_SYMBOLS = [
     "sp_status_string", "sp_last_error", "sp_profile_enable", "sp_profile_read", "sp_workspace_bytes",
     "sp_dense_attn_with_block_scores", "sp_build_block_mask",
     "sp_block_sparse_attn", "sp_prefill_layer",
+    "sp_score_workspace_bytes", "sp_mask_workspace_bytes", "sp_block_mean_logit_scores",
+    "sp_build_block_mask_global", "sp_prefill_layer_modes",
 ]
+
+SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT = 0, 1
+SP_SELECT_PER_ROW, SP_SELECT_GLOBAL = 0, 1
 
 
 class SpShape(ctypes.Structure):
@@ -72,6 +77,18 @@ def lib() -> ctypes.CDLL:
         L.sp_prefill_layer.restype = ctypes.c_int
         L.sp_prefill_layer.argtypes = [sp, vp, vp, vp, ip, ip, ctypes.c_int32, ctypes.c_float, vp, fp, vp, vp,
                                        vp, ctypes.c_size_t, vp]
+        L.sp_score_workspace_bytes.restype = ctypes.c_int
+        L.sp_score_workspace_bytes.argtypes = [sp, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
+        L.sp_mask_workspace_bytes.restype = ctypes.c_int
+        L.sp_mask_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
+        L.sp_block_mean_logit_scores.restype = ctypes.c_int
+        L.sp_block_mean_logit_scores.argtypes = [sp, vp, vp, ip, ctypes.c_int32, fp, vp, ctypes.c_size_t, vp]
+        L.sp_build_block_mask_global.restype = ctypes.c_int
+        L.sp_build_block_mask_global.argtypes = [fp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                                 ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.sp_prefill_layer_modes.restype = ctypes.c_int
+        L.sp_prefill_layer_modes.argtypes = [sp, vp, vp, vp, ip, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_int32,
+                                             ctypes.c_int32, vp, fp, vp, vp, vp, ctypes.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -111,7 +128,7 @@ def shape_of(q, k, o=None, block: int = 128, softmax_scale: float = 0.0) -> SpSh
     return s
 
 
-KERNEL_KINDS = ("pack", "dense", "mask", "sparse")
+KERNEL_KINDS = ("pack", "dense", "mask", "sparse", "score")
 
 
 def sp_profile_enable(on: bool):
@@ -120,8 +137,8 @@ def sp_profile_enable(on: bool):
 
 def sp_profile_read(reset: bool = True):
     """{kind: (total ms, launches)} since the last reset; synchronise the stream first."""
-    ms = (ctypes.c_float * 4)()
-    n = (ctypes.c_int32 * 4)()
+    ms = (ctypes.c_float * len(KERNEL_KINDS))()
+    n = (ctypes.c_int32 * len(KERNEL_KINDS))()
     _check(lib().sp_profile_read(ms, n, 1 if reset else 0))
     return {k: (float(ms[a]), int(n[a])) for a, k in enumerate(KERNEL_KINDS)}
 
@@ -158,3 +175,40 @@ def sp_prefill_layer(shape: SpShape, q, k, v, head_to_cluster, pivot_heads, gamm
         ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_to_cluster), _ids(pivot_heads),
         len(pivot_heads), ctypes.c_float(gamma), _ptr(o), _ptr(block_scores), _ptr(kb_idx), _ptr(kb_cnt),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def sp_score_workspace_bytes(shape: SpShape, n_heads: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().sp_score_workspace_bytes(ctypes.byref(shape), n_heads, ctypes.byref(n)))
+    return int(n.value)
+
+
+def sp_mask_workspace_bytes(n_maps: int, nqb: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().sp_mask_workspace_bytes(n_maps, nqb, ctypes.byref(n)))
+    return int(n.value)
+
+
+def sp_block_mean_logit_scores(shape: SpShape, q, k, head_ids, block_scores, workspace):
+    _check(lib().sp_block_mean_logit_scores(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ids(head_ids), len(head_ids), _ptr(block_scores),
+        _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def sp_build_block_mask_global(block_scores, n_maps: int, nqb: int, nkb: int, gamma: float, forced: bool,
+                               kb_idx, kb_cnt, workspace):
+    _check(lib().sp_build_block_mask_global(_ptr(block_scores), n_maps, nqb, nkb, ctypes.c_float(gamma),
+                                            1 if forced else 0, _ptr(kb_idx), _ptr(kb_cnt), _ptr(workspace),
+                                            _nbytes(workspace), _stream()))
+
+
+def sp_prefill_layer_modes(shape: SpShape, q, k, v, head_to_cluster, pivot_heads, gamma: float, score_mode: int,
+                           select_mode: int, o, block_scores, kb_idx, kb_cnt, workspace):
+    _check(lib().sp_prefill_layer_modes(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_to_cluster), _ids(pivot_heads),
+        len(pivot_heads), ctypes.c_float(gamma), int(score_mode), int(select_mode), _ptr(o), _ptr(block_scores),
+        _ptr(kb_idx), _ptr(kb_cnt), _ptr(workspace), _nbytes(workspace), _stream()))

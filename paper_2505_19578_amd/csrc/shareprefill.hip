@@ -12,6 +12,9 @@
 //                    DENSE=false walks a per-row key-block index list (Sec. 5.1 A(Q,K,V,M)).
 //   mask_kernel      Alg. 2 per query-block row in exact integer arithmetic, one wavefront
 //                    per row: threshold search + ballot/popcount prefix sums.
+//   block_pool_kernel, mean_logit_softmax_kernel, gsel_*_kernel
+//                    the pattern construction as the paper prints it: row softmax of the
+//                    block-mean QK logits (Sec. 5.2) and Alg. 2 over the flattened map.
 //
 // MFMA operand mapping (v_mfma_f32_32x32x16_bf16, 64 lanes, lane = 32*h + c):
 //   A (32 x 16): lane holds row c, k = 8h .. 8h+7        B (16 x 32): lane holds column c, same k
@@ -49,7 +52,7 @@ thread_local char g_err[512] = "";
 
 // Optional per-kernel timing (sp_profile_enable / sp_profile_read): every launch is bracketed
 // by two HIP events on the caller's stream.  Process-wide, not thread-safe; meant for benches.
-enum KernelKind { KK_PACK = 0, KK_DENSE = 1, KK_MASK = 2, KK_SPARSE = 3, KK_COUNT = 4 };
+enum KernelKind { KK_PACK = 0, KK_DENSE = 1, KK_MASK = 2, KK_SPARSE = 3, KK_SCORE = 4, KK_COUNT = 5 };
 struct ProfRec {
   int kind;
   hipEvent_t e0, e1;
@@ -720,6 +723,326 @@ __global__ __launch_bounds__(256) void mask_kernel(const float *__restrict__ sco
 }
 
 // ---------------------------------------------------------------------------------------------
+// pattern construction as printed in the paper (Sec. 5.2 "Sparse Attention Computation" and
+// "Pivotal Pattern Construction"; Alg. 2): block-mean logits -> row softmax -> one selection over
+// the flattened, globally normalised map
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
+
+struct PoolParams {
+  const uint16_t *q, *k;
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
+  int nqb, group, n_heads;
+  float *qsum;   // [b][n][nqb][D]   sum of the block's queries
+  float *ksumT;  // [b][n][D][nqb]   sum of the block's keys, block index fastest
+  float *diag;   // [b][n][nqb]      sum over the diagonal block's causal entries of q_t . k_s
+  int32_t head_ids[SP_MAX_HEADS];
+};
+
+// The average of q_t . k_s over a full block is (sum_t q_t) . (sum_s k_s) / B^2, so the block-mean
+// logits need only per-block sums of Q and K.  The diagonal block keeps s <= t only:
+// sum_t q_t . (sum_{s<=t} k_s), a running key sum walked once.  One thread per head dimension.
+template <int D, int B>
+__global__ __launch_bounds__(D) void block_pool_kernel(PoolParams p) {
+  const int i = blockIdx.x, n = blockIdx.y, b = blockIdx.z, e = threadIdx.x;
+  const int head = p.head_ids[n];
+  const uint16_t *qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * B * p.q_st + (int64_t)head * p.q_sh + e;
+  const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)i * B * p.k_st + (int64_t)(head / p.group) * p.k_sh + e;
+  float run = 0.f, qs = 0.f, acc = 0.f;
+#pragma unroll 8
+  for (int t = 0; t < B; ++t) {
+    const float kk = bf16_bits_to_float(kp[(int64_t)t * p.k_st]);
+    const float qq = bf16_bits_to_float(qp[(int64_t)t * p.q_st]);
+    run += kk;
+    qs += qq;
+    acc = fmaf(qq, run, acc);
+  }
+  const int64_t hb = (int64_t)b * p.n_heads + n;
+  p.qsum[(hb * p.nqb + i) * D + e] = qs;
+  p.ksumT[(hb * D + e) * p.nqb + i] = run;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if constexpr (D == 64) {
+    if (e == 0) p.diag[hb * p.nqb + i] = acc;
+  } else {
+    __shared__ float part[D / 64];
+    if ((e & 63) == 0) part[e >> 6] = acc;
+    __syncthreads();
+    if (e == 0) {
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < D / 64; ++w) s += part[w];
+      p.diag[hb * p.nqb + i] = s;
+    }
+  }
+}
+
+// Four query-block rows per workgroup: thread j forms the four pooled dot products against key block j
+// (block index fastest in ksumT, so the loads coalesce), then one wavefront per row applies the row
+// softmax in place (Alg. 2, first step).  Entries beyond the diagonal are written as 0.
+template <int D>
+__global__ __launch_bounds__(256) void mean_logit_softmax_kernel(const float *__restrict__ qsum,
+                                                                 const float *__restrict__ ksumT,
+                                                                 const float *__restrict__ diag,
+                                                                 float *__restrict__ scores, int nqb,
+                                                                 float c_full, float c_diag) {
+  constexpr int R = 4;
+  __shared__ float qs[R][D];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int i0 = blockIdx.x * R;
+  const int64_t hb = blockIdx.y;
+  for (int x = tid; x < R * D; x += 256) {
+    const int r = x / D, e = x % D;
+    qs[r][e] = (i0 + r < nqb) ? qsum[(hb * nqb + i0 + r) * D + e] : 0.f;
+  }
+  __syncthreads();
+  const float *kT = ksumT + hb * D * nqb;
+  const int imax = min(i0 + R - 1, nqb - 1);
+  for (int j = tid; j <= imax; j += 256) {
+    float acc[R] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int e = 0; e < D; ++e) {
+      const float kv = kT[(int64_t)e * nqb + j];
+#pragma unroll
+      for (int r = 0; r < R; ++r) acc[r] = fmaf(qs[r][e], kv, acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int i = i0 + r;
+      if (i < nqb && j <= i)
+        scores[(hb * nqb + i) * nqb + j] = (j < i) ? acc[r] * c_full : diag[hb * nqb + i] * c_diag;
+    }
+  }
+  __syncthreads();
+  const int i = i0 + w;
+  if (i >= nqb) return;
+  float *row = scores + (hb * nqb + i) * nqb;
+  float mx = -INFINITY;
+  for (int j = lane; j <= i; j += 64) mx = fmaxf(mx, row[j]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  float den = 0.f;
+  for (int j = lane; j <= i; j += 64) den += expf(row[j] - mx);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off, 64);
+  for (int j = lane; j < nqb; j += 64) row[j] = (j <= i) ? expf(row[j] - mx) / den : 0.f;
+}
+
+// ---- Alg. 2 over the flattened map, exact integers -------------------------------------------
+// With u = the 24-bit score, T = ceil(gamma_q * total / 2^24): the kept set is every entry above
+// a threshold value v* plus the first `need` entries equal to v* in flat (row-major) order, where v*
+// is the largest value with sum_{u >= v*} u >= T.  v* is found by two 12-bit histogram passes
+// (sums of u per bin), the ties are ranked by a per-row count and a prefix sum over rows.
+constexpr int GS_BINS = 4104;  // 4097 used by the first pass (u can equal 2^24), padded
+struct GselState {
+  uint64_t T, above, need;
+  uint32_t bin_hi, vstar;
+  uint32_t pad[8];
+};
+static_assert(sizeof(GselState) == 64, "GselState layout");
+
+struct GselView {
+  unsigned long long *hist1, *hist2;
+  GselState *state;
+  uint32_t *row_ties, *row_before;
+};
+__host__ __device__ inline size_t gsel_map_bytes(int nqb) {
+  return (size_t)2 * GS_BINS * 8 + sizeof(GselState) + (((size_t)nqb * 8 + 255) / 256) * 256;
+}
+__device__ __forceinline__ GselView gsel_view(char *scratch, int map, int nqb) {
+  char *base = scratch + (size_t)map * gsel_map_bytes(nqb);
+  GselView v;
+  v.hist1 = reinterpret_cast<unsigned long long *>(base);
+  v.hist2 = v.hist1 + GS_BINS;
+  v.state = reinterpret_cast<GselState *>(v.hist2 + GS_BINS);
+  v.row_ties = reinterpret_cast<uint32_t *>(v.state + 1);
+  v.row_before = v.row_ties + nqb;
+  return v;
+}
+
+__global__ __launch_bounds__(256) void gsel_zero_kernel(char *scratch, int nqb) {
+  GselView v = gsel_view(scratch, blockIdx.x, nqb);
+  for (int x = threadIdx.x; x < 2 * GS_BINS; x += 256) v.hist1[x] = 0ull;
+}
+
+template <int PASS>
+__global__ __launch_bounds__(256) void gsel_hist_kernel(const float *__restrict__ scores, int nqb, char *scratch) {
+  __shared__ unsigned long long h[GS_BINS];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int map = blockIdx.y;
+  GselView v = gsel_view(scratch, map, nqb);
+  for (int x = tid; x < GS_BINS; x += 256) h[x] = 0ull;
+  __syncthreads();
+  const uint32_t bin_hi = (PASS == 2) ? v.state->bin_hi : 0u;
+  unsigned long long low = 0ull;  // first pass: bin 0 holds most of a softmaxed map; keep it out of the LDS atomics
+  for (int row = blockIdx.x * 4 + w; row < nqb; row += gridDim.x * 4) {
+    const float *src = scores + ((int64_t)map * nqb + row) * nqb;
+    for (int j = lane; j <= row; j += 64) {
+      const uint32_t u = quantise24(src[j]);
+      if (PASS == 1) {
+        const uint32_t bin = u >> 12;
+        if (bin == 0)
+          low += u;
+        else
+          atomicAdd(&h[bin], (unsigned long long)u);
+      } else if (u != 0u && (u >> 12) == bin_hi) {
+        atomicAdd(&h[u & 4095u], (unsigned long long)u);
+      }
+    }
+  }
+  if (PASS == 1) {
+    low = wave_sum_u64(low);
+    if (lane == 0 && low) atomicAdd(&h[0], low);
+  }
+  __syncthreads();
+  unsigned long long *g = (PASS == 1) ? v.hist1 : v.hist2;
+  for (int x = tid; x < GS_BINS; x += 256)
+    if (h[x]) atomicAdd(&g[x], h[x]);
+}
+
+// One workgroup of 1024 threads per map.  Thread t owns bins [5t, 5t+5); a suffix sum over threads
+// locates the bin in which the running sum from the top first reaches the target.
+template <int PASS>
+__global__ __launch_bounds__(1024) void gsel_scan_kernel(char *scratch, int nqb, uint32_t gq) {
+  __shared__ unsigned long long wt[16];
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  GselView v = gsel_view(scratch, blockIdx.x, nqb);
+  const unsigned long long *hist = (PASS == 1) ? v.hist1 : v.hist2;
+  constexpr int NB = (PASS == 1) ? 4097 : 4096;
+  unsigned long long mine[5], sum = 0ull;
+#pragma unroll
+  for (int x = 0; x < 5; ++x) {
+    const int bin = 5 * t + x;
+    mine[x] = (bin < NB) ? hist[bin] : 0ull;
+    sum += mine[x];
+  }
+  unsigned long long incl = sum;  // sum over lanes >= this one
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned long long y = __shfl_down(incl, off, 64);
+    if (lane + off < 64) incl += y;
+  }
+  if (lane == 0) wt[w] = incl;
+  __syncthreads();
+  unsigned long long above = incl - sum, tot = 0ull;
+  for (int x = 0; x < 16; ++x) {
+    tot += wt[x];
+    if (x > w) above += wt[x];
+  }
+  unsigned long long T;
+  if (PASS == 1) {
+    const unsigned long long th = tot >> 24, tl = tot & 0xFFFFFFull;
+    T = (unsigned long long)gq * th + (((unsigned long long)gq * tl + 0xFFFFFFull) >> 24);  // ceil(gq * tot / 2^24)
+    if (T < 1) T = 1;
+    if (tot == 0ull) {
+      if (t == 0) {
+        v.state->T = 0;
+        v.state->above = 0;
+        v.state->need = 0;
+        v.state->bin_hi = 0xFFFFFFFFu;
+        v.state->vstar = 0xFFFFFFFFu;  // nothing reaches it
+      }
+      return;
+    }
+  } else {
+    if (v.state->vstar == 0xFFFFFFFFu && v.state->bin_hi == 0xFFFFFFFFu) return;  // empty map
+    T = v.state->T - v.state->above;
+  }
+  if (above < T && T <= above + sum) {  // exactly one thread
+    unsigned long long a = above;
+    for (int x = 4; x >= 0; --x) {
+      if (a + mine[x] >= T) {
+        const uint32_t bin = (uint32_t)(5 * t + x);
+        if (PASS == 1) {
+          v.state->T = T;
+          v.state->above = a;
+          v.state->bin_hi = bin;
+          v.state->vstar = 0u;
+        } else {
+          const uint32_t vs = (v.state->bin_hi << 12) | bin;
+          const unsigned long long gt = v.state->above + a;  // sum of everything above v*
+          v.state->vstar = vs;
+          v.state->need = (v.state->T - gt + vs - 1) / vs;
+        }
+        break;
+      }
+      a += mine[x];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void gsel_row_ties_kernel(const float *__restrict__ scores, int nqb, char *scratch) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
+  if (row >= nqb) return;
+  GselView v = gsel_view(scratch, map, nqb);
+  const uint32_t vstar = v.state->vstar;
+  const float *src = scores + ((int64_t)map * nqb + row) * nqb;
+  uint32_t n = 0;
+  for (int j = lane; j <= row; j += 64) n += (quantise24(src[j]) == vstar) ? 1u : 0u;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) n += __shfl_xor(n, off, 64);
+  if (lane == 0) v.row_ties[row] = n;
+}
+
+// exclusive prefix sum of row_ties over the rows of one map (flat order = row-major)
+__global__ __launch_bounds__(1024) void gsel_row_scan_kernel(int nqb, char *scratch) {
+  __shared__ uint32_t wt[16];
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  GselView v = gsel_view(scratch, blockIdx.x, nqb);
+  const int per = (nqb + 1023) / 1024;
+  const int r0 = t * per, r1 = min(r0 + per, nqb);
+  uint32_t sum = 0;
+  for (int r = r0; r < r1; ++r) sum += v.row_ties[r];
+  uint32_t incl = sum;  // sum over lanes <= this one
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t y = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += y;
+  }
+  if (lane == 63) wt[w] = incl;
+  __syncthreads();
+  uint32_t before = incl - sum;
+  for (int x = 0; x < w; ++x) before += wt[x];
+  for (int r = r0; r < r1; ++r) {
+    v.row_before[r] = before;
+    before += v.row_ties[r];
+  }
+}
+
+// one wavefront per row: ascending list of the kept key blocks (+ sink and diagonal when forced)
+__global__ __launch_bounds__(256) void gsel_emit_kernel(const float *__restrict__ scores, int nqb, char *scratch,
+                                                        int forced, int32_t *__restrict__ kb_idx,
+                                                        int32_t *__restrict__ kb_cnt) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
+  if (i >= nqb) return;
+  GselView v = gsel_view(scratch, map, nqb);
+  const uint32_t vstar = v.state->vstar;
+  const uint64_t need = v.state->need;
+  const uint64_t before = v.row_before[i];
+  const float *src = scores + ((int64_t)map * nqb + i) * nqb;
+  int32_t *out = kb_idx + ((int64_t)map * nqb + i) * nqb;
+  const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  uint32_t ties_seen = 0, n_out = 0;
+  for (int j0 = 0; j0 <= i; j0 += 64) {
+    const int j = j0 + lane;
+    const uint32_t x = (j <= i) ? quantise24(src[j]) : 0u;
+    const bool tie = (j <= i) && (x == vstar);
+    const uint64_t tmask = __ballot(tie);
+    const uint64_t trank = before + ties_seen + __popcll(tmask & lt);
+    ties_seen += __popcll(tmask);
+    const bool sel = (j <= i) && ((x > vstar && vstar != 0xFFFFFFFFu) || (tie && trank < need) ||
+                                  (forced && (j == 0 || j == i)));
+    const uint64_t smask = __ballot(sel);
+    if (sel) out[n_out + __popcll(smask & lt)] = j;
+    n_out += __popcll(smask);
+  }
+  for (int pos = n_out + lane; pos < nqb; pos += 64) out[pos] = -1;
+  if (lane == 0) kb_cnt[(int64_t)map * nqb + i] = (int32_t)n_out;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -783,6 +1106,22 @@ size_t pack_bytes(const sp_shape *s) {
 size_t lws_bytes(const sp_shape *s, int n_dense) {
   const size_t nqb = s->seq / s->block;
   return align_up((size_t)s->batch * n_dense * nqb * nqb * s->block * sizeof(float), 256);
+}
+
+// scratch of the paper-literal pattern construction for n heads (= maps) per batch entry:
+// [qsum | ksumT | diag | per-map selection scratch]
+struct PatternLayout {
+  size_t qsum, ksumT, diag, gsel, total;
+};
+PatternLayout pattern_layout(const sp_shape *s, int n) {
+  const size_t nqb = s->seq / s->block, maps = (size_t)s->batch * n;
+  PatternLayout L;
+  L.qsum = 0;
+  L.ksumT = L.qsum + align_up(maps * nqb * s->head_dim * sizeof(float), 256);
+  L.diag = L.ksumT + align_up(maps * nqb * s->head_dim * sizeof(float), 256);
+  L.gsel = L.diag + align_up(maps * nqb * sizeof(float), 256);
+  L.total = L.gsel + align_up(maps * gsel_map_bytes((int)nqb), 256);
+  return L;
 }
 
 sp_status check_ptr16(const void *p, const char *name) {
@@ -938,6 +1277,80 @@ sp_status launch_mask(const float *scores, int n_maps, int nqb, int nkb, float g
   return hip_check(hipGetLastError(), "mask_kernel launch");
 }
 
+// row softmax of the block-mean logits of the listed heads into scores[b][n][nqb][nkb]
+sp_status launch_mean_logit_scores(const sp_shape *s, const void *q, const void *k, const int32_t *heads, int n,
+                                   float *scores, char *pattern_ws, hipStream_t st) {
+  if ((int64_t)s->batch * n > 65535) {
+    set_err("batch * heads = %lld exceeds 65535", (long long)s->batch * n);
+    return SP_ERR_UNSUPPORTED;
+  }
+  const PatternLayout L = pattern_layout(s, n);
+  const int nqb = s->seq / s->block;
+  PoolParams pp;
+  memset(&pp, 0, sizeof(pp));
+  pp.q = (const uint16_t *)q;
+  pp.k = (const uint16_t *)k;
+  pp.q_sb = s->q_stride_b;
+  pp.q_st = s->q_stride_t;
+  pp.q_sh = s->q_stride_h;
+  pp.k_sb = s->kv_stride_b;
+  pp.k_st = s->kv_stride_t;
+  pp.k_sh = s->kv_stride_h;
+  pp.nqb = nqb;
+  pp.group = s->n_q_heads / s->n_kv_heads;
+  pp.n_heads = n;
+  pp.qsum = (float *)(pattern_ws + L.qsum);
+  pp.ksumT = (float *)(pattern_ws + L.ksumT);
+  pp.diag = (float *)(pattern_ws + L.diag);
+  for (int a = 0; a < n; ++a) pp.head_ids[a] = heads[a];
+  const float scale = (s->softmax_scale > 0.f) ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
+  const float B = (float)s->block;
+  const float c_full = scale / (B * B), c_diag = scale / (B * (B + 1.f) * 0.5f);
+  ProfScope prof(KK_SCORE, st);
+  dim3 gpool(nqb, n, s->batch), glog((nqb + 3) / 4, s->batch * n);
+#define SP_POOL(D_, B_) hipLaunchKernelGGL((block_pool_kernel<D_, B_>), gpool, dim3(D_), 0, st, pp)
+  if (s->head_dim == 128 && s->block == 128)
+    SP_POOL(128, 128);
+  else if (s->head_dim == 128 && s->block == 64)
+    SP_POOL(128, 64);
+  else if (s->head_dim == 64 && s->block == 128)
+    SP_POOL(64, 128);
+  else
+    SP_POOL(64, 64);
+#undef SP_POOL
+  sp_status rc = hip_check(hipGetLastError(), "block_pool_kernel launch");
+  if (rc) return rc;
+  if (s->head_dim == 128)
+    hipLaunchKernelGGL(mean_logit_softmax_kernel<128>, glog, dim3(256), 0, st, pp.qsum, pp.ksumT, pp.diag, scores,
+                       nqb, c_full, c_diag);
+  else
+    hipLaunchKernelGGL(mean_logit_softmax_kernel<64>, glog, dim3(256), 0, st, pp.qsum, pp.ksumT, pp.diag, scores,
+                       nqb, c_full, c_diag);
+  return hip_check(hipGetLastError(), "mean_logit_softmax_kernel launch");
+}
+
+// Alg. 2 over each flattened map; `scratch` holds n_maps * gsel_map_bytes(nqb) bytes
+sp_status launch_mask_global(const float *scores, int n_maps, int nqb, float gamma, int forced, int32_t *kb_idx,
+                             int32_t *kb_cnt, char *scratch, hipStream_t st) {
+  if (n_maps > 65535) {
+    set_err("%d maps exceed 65535", n_maps);
+    return SP_ERR_UNSUPPORTED;
+  }
+  const uint32_t gq = (uint32_t)rintf(gamma * 16777216.f);
+  const int row_groups = (nqb + 3) / 4;
+  const dim3 ghist(std::min(row_groups, 64), n_maps), grows(row_groups, n_maps);
+  ProfScope prof(KK_MASK, st);
+  hipLaunchKernelGGL(gsel_zero_kernel, dim3(n_maps), dim3(256), 0, st, scratch, nqb);
+  hipLaunchKernelGGL(gsel_hist_kernel<1>, ghist, dim3(256), 0, st, scores, nqb, scratch);
+  hipLaunchKernelGGL(gsel_scan_kernel<1>, dim3(n_maps), dim3(1024), 0, st, scratch, nqb, gq);
+  hipLaunchKernelGGL(gsel_hist_kernel<2>, ghist, dim3(256), 0, st, scores, nqb, scratch);
+  hipLaunchKernelGGL(gsel_scan_kernel<2>, dim3(n_maps), dim3(1024), 0, st, scratch, nqb, gq);
+  hipLaunchKernelGGL(gsel_row_ties_kernel, grows, dim3(256), 0, st, scores, nqb, scratch);
+  hipLaunchKernelGGL(gsel_row_scan_kernel, dim3(n_maps), dim3(1024), 0, st, nqb, scratch);
+  hipLaunchKernelGGL(gsel_emit_kernel, grows, dim3(256), 0, st, scores, nqb, scratch, forced, kb_idx, kb_cnt);
+  return hip_check(hipGetLastError(), "global selection kernels launch");
+}
+
 sp_status check_ws(const void *ws, size_t have, size_t need) {
   if (need == 0) return SP_OK;
   if (!ws) {
@@ -1021,7 +1434,37 @@ sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_
     set_err("n_dense_heads %d outside [0, %d]", n_dense_heads, shape->n_q_heads);
     return SP_ERR_INVALID_ARG;
   }
-  *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads);
+  *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads) + pattern_layout(shape, n_dense_heads).total;
+  return SP_OK;
+}
+
+sp_status sp_score_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *bytes) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if (!bytes) {
+    set_err("bytes is NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n_heads < 0 || n_heads > shape->n_q_heads) {
+    set_err("n_heads %d outside [0, %d]", n_heads, shape->n_q_heads);
+    return SP_ERR_INVALID_ARG;
+  }
+  *bytes = pattern_layout(shape, n_heads).gsel;  // the pooled sums only
+  return SP_OK;
+}
+
+sp_status sp_mask_workspace_bytes(int32_t n_maps, int32_t nqb, size_t *bytes) {
+  g_err[0] = 0;
+  if (!bytes) {
+    set_err("bytes is NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n_maps <= 0 || nqb <= 0 || nqb > 32768) {
+    set_err("n_maps must be positive and nqb in [1, 32768]");
+    return SP_ERR_INVALID_ARG;
+  }
+  *bytes = align_up((size_t)n_maps * gsel_map_bytes(nqb), 256);
   return SP_OK;
 }
 
@@ -1124,10 +1567,58 @@ sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void 
   return launch_attn<false>(shape, ap, hl, st);
 }
 
-sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
-                           const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
-                           float gamma, void *o, float *block_scores, int32_t *kb_idx, int32_t *kb_cnt,
-                           void *workspace, size_t workspace_bytes, void *hip_stream) {
+sp_status sp_block_mean_logit_scores(const sp_shape *shape, const void *q, const void *k, const int32_t *head_ids,
+                                     int32_t n_heads, float *block_scores, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k"))) return rc;
+  if ((rc = check_heads(shape, head_ids, n_heads, "head_ids"))) return rc;
+  if (!block_scores || ((uintptr_t)block_scores % 4)) {
+    set_err("block_scores is NULL or misaligned");
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((rc = check_ws(workspace, workspace_bytes, pattern_layout(shape, n_heads).gsel))) return rc;
+  return launch_mean_logit_scores(shape, q, k, head_ids, n_heads, block_scores, (char *)workspace,
+                                  (hipStream_t)hip_stream);
+}
+
+sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb, float gamma,
+                                     int32_t forced, int32_t *kb_idx, int32_t *kb_cnt, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  if (!block_scores || !kb_idx || !kb_cnt) {
+    set_err("block_scores / kb_idx / kb_cnt must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n_maps <= 0 || nqb <= 0 || nkb <= 0) {
+    set_err("n_maps, nqb, nkb must be positive");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (nqb != nkb) {
+    set_err("nqb (%d) != nkb (%d): causal prefill maps are square", nqb, nkb);
+    return SP_ERR_INVALID_ARG;
+  }
+  if (nkb > 32768 || n_maps > 65535) {
+    set_err("nkb %d exceeds 32768 or n_maps %d exceeds 65535", nkb, n_maps);
+    return SP_ERR_UNSUPPORTED;
+  }
+  if (!(gamma > 0.f) || gamma > 1.f) {
+    set_err("gamma %g outside (0, 1]", (double)gamma);
+    return SP_ERR_INVALID_ARG;
+  }
+  sp_status rc = check_ws(workspace, workspace_bytes, align_up((size_t)n_maps * gsel_map_bytes(nqb), 256));
+  if (rc) return rc;
+  return launch_mask_global(block_scores, n_maps, nqb, gamma, forced != 0, kb_idx, kb_cnt, (char *)workspace,
+                            (hipStream_t)hip_stream);
+}
+
+sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                 const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                                 float gamma, int32_t score_mode, int32_t select_mode, void *o, float *block_scores,
+                                 int32_t *kb_idx, int32_t *kb_cnt, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream) {
   g_err[0] = 0;
   sp_status rc = check_shape(shape);
   if (rc) return rc;
@@ -1136,6 +1627,11 @@ sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, 
     return rc;
   if (!head_to_cluster || !pivot_heads || !block_scores || !kb_idx || !kb_cnt) {
     set_err("head_to_cluster / pivot_heads / block_scores / kb_idx / kb_cnt must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((score_mode != SP_SCORE_BLOCK_MASS && score_mode != SP_SCORE_MEAN_LOGIT) ||
+      (select_mode != SP_SELECT_PER_ROW && select_mode != SP_SELECT_GLOBAL)) {
+    set_err("unknown score_mode %d / select_mode %d", score_mode, select_mode);
     return SP_ERR_INVALID_ARG;
   }
   const int Hq = shape->n_q_heads;
@@ -1165,21 +1661,32 @@ sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, 
     }
     is_pivot[ph] = true;
   }
-  const size_t need = pack_bytes(shape) + lws_bytes(shape, n_clusters);
+  const bool mass = score_mode == SP_SCORE_BLOCK_MASS;
+  const bool pattern_ws = !mass || select_mode == SP_SELECT_GLOBAL;
+  const size_t off_lws = pack_bytes(shape);
+  const size_t off_pat = off_lws + (mass ? lws_bytes(shape, n_clusters) : 0);
+  const PatternLayout PL = pattern_layout(shape, n_clusters);
+  const size_t need = off_pat + (pattern_ws ? PL.total : 0);
   if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   const int nqb = shape->seq / shape->block;
+  char *ws = (char *)workspace;
 
   if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
-  // 1. pivots: dense attention + block-mass scores (Alg. 1 line 8 with M = ones, Alg. 4)
+  // 1. pivots: dense attention (Alg. 4: no pattern yet => all ones) and their block score map
+  //    (Alg. 1 line 8): block mass from the same sweep, or the row softmax of the block-mean logits
   AttnParams ap;
   fill_attn(ap, shape, q, workspace, o);
   HeadList hl;
   hl.n = n_clusters;
   for (int c = 0; c < n_clusters; ++c) hl.head[c] = pivot_heads[c];
-  ap.lws = (float *)((char *)workspace + pack_bytes(shape));
-  ap.scores = block_scores;
+  if (mass) {
+    ap.lws = (float *)(ws + off_lws);
+    ap.scores = block_scores;
+  }
   if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
+  if (!mass && (rc = launch_mean_logit_scores(shape, q, k, pivot_heads, n_clusters, block_scores, ws + off_pat, st)))
+    return rc;
   // 2. heads outside every cluster: dense, no scores
   fill_attn(ap, shape, q, workspace, o);
   hl.n = 0;
@@ -1188,9 +1695,13 @@ sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, 
   if (hl.n) {
     if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
   }
-  // 3. one pattern per (batch, cluster) (Alg. 2)
-  if ((rc = launch_mask(block_scores, shape->batch * n_clusters, nqb, nqb, gamma, kb_idx, kb_cnt, nullptr, st)))
-    return rc;
+  // 3. one pattern per (batch, cluster) (Alg. 2: per query-block row, or over the flattened map)
+  if (select_mode == SP_SELECT_PER_ROW)
+    rc = launch_mask(block_scores, shape->batch * n_clusters, nqb, nqb, gamma, kb_idx, kb_cnt, nullptr, st);
+  else
+    rc = launch_mask_global(block_scores, shape->batch * n_clusters, nqb, gamma, 1, kb_idx, kb_cnt,
+                            ws + off_pat + PL.gsel, st);
+  if (rc) return rc;
   // 4. remaining heads share their cluster's pattern (Alg. 4) and run block-sparse (Sec. 5.1)
   fill_attn(ap, shape, q, workspace, o);
   hl.n = 0;
@@ -1207,6 +1718,15 @@ sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, 
     if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
   }
   return SP_OK;
+}
+
+sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
+                           const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                           float gamma, void *o, float *block_scores, int32_t *kb_idx, int32_t *kb_cnt,
+                           void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return sp_prefill_layer_modes(shape, q, k, v, head_to_cluster, pivot_heads, n_clusters, gamma, SP_SCORE_BLOCK_MASS,
+                                SP_SELECT_PER_ROW, o, block_scores, kb_idx, kb_cnt, workspace, workspace_bytes,
+                                hip_stream);
 }
 
 }  // extern "C"

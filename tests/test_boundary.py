@@ -36,7 +36,17 @@ def test_workspace_bytes_and_shape_validation():
     s = _shape(sp)
     pack = 1 * 4 * 1024 * 64 * 2 * 2
     assert sp.sp_workspace_bytes(s, 0) == pack
-    assert sp.sp_workspace_bytes(s, 2) == pack + 2 * 16 * 16 * 64 * 4
+    score_ws = 2 * (2 * 16 * 64 * 4) + 256                       # per-block sums of Q and K + diagonal sums
+    mask_ws = -(-(2 * (2 * 4104 * 8 + 64 + 256)) // 256) * 256   # two histograms + state + per-row counters, per map
+    assert sp.sp_score_workspace_bytes(s, 2) == score_ws
+    assert sp.sp_mask_workspace_bytes(2, 16) == mask_ws
+    assert sp.sp_workspace_bytes(s, 2) == pack + 2 * 16 * 16 * 64 * 4 + score_ws + mask_ws
+    with pytest.raises(sp.SpError):
+        sp.sp_mask_workspace_bytes(0, 16)
+    with pytest.raises(sp.SpError):
+        sp.sp_mask_workspace_bytes(1, 40000)
+    with pytest.raises(sp.SpError):
+        sp.sp_score_workspace_bytes(s, 5)
     for bad, status in [
         (dict(seq=1000), "SP_ERR_UNSUPPORTED"),
         (dict(head_dim=96), "SP_ERR_UNSUPPORTED"),
@@ -88,6 +98,29 @@ def test_calls_reject_bad_arguments_without_launching():
     piv = (ctypes.c_int32 * 2)(0, 2)
     rc = L.sp_prefill_layer(ctypes.byref(s), fake, fake, fake, h2c, piv, 2, ctypes.c_float(0.9), fake, fake, fake,
                             fake, fake, 16, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    # pattern construction as printed: scores, global selection, fused call with modes
+    rc = L.sp_block_mean_logit_scores(ctypes.byref(s), fake, None, ids, 1, fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"k is NULL" in L.sp_last_error()
+    rc = L.sp_block_mean_logit_scores(ctypes.byref(s), fake, fake, ids, 1, None, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    rc = L.sp_block_mean_logit_scores(ctypes.byref(s), fake, fake, ids, 1, fake, fake, 64, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    rc = L.sp_build_block_mask_global(fake, 1, 16, 16, ctypes.c_float(1.5), 1, fake, fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    rc = L.sp_build_block_mask_global(fake, 1, 16, 8, ctypes.c_float(0.9), 1, fake, fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    rc = L.sp_build_block_mask_global(fake, 70000, 16, 16, ctypes.c_float(0.9), 1, fake, fake, fake, 1 << 40, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_UNSUPPORTED"
+    rc = L.sp_build_block_mask_global(fake, 1, 16, 16, ctypes.c_float(0.9), 1, fake, fake, fake, 1024, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    rc = L.sp_build_block_mask_global(fake, 1, 16, 16, ctypes.c_float(0.9), 1, fake, fake, None, 0, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    rc = L.sp_prefill_layer_modes(ctypes.byref(s), fake, fake, fake, h2c, piv, 2, ctypes.c_float(0.9), 2, 0, fake,
+                                  fake, fake, fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"score_mode" in L.sp_last_error()
+    rc = L.sp_prefill_layer_modes(ctypes.byref(s), fake, fake, fake, h2c, piv, 2, ctypes.c_float(0.9), 1, 1, fake,
+                                  fake, fake, fake, fake, 16, None)
     assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
 
 
