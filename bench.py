@@ -187,8 +187,9 @@ def main() -> int:
     props = torch.cuda.get_device_properties(0)
     out["roofline"]["peak_source"] = "published MI355X dense bf16 MFMA figure (256 CUs x 4096 flop/clk x 2.4 GHz)"
     out["roofline"]["board"] = {"name": props.name, "cus": props.multi_processor_count,
-                                "max_engine_clock_mhz": props.clock_rate / 1e3,
-                                "derived_peak_tflops": props.multi_processor_count * 4096 * props.clock_rate * 1e3 / 1e12}
+                                "max_engine_clock_mhz": getattr(props, "clock_rate", 0) / 1e3,
+                                "derived_peak_tflops": props.multi_processor_count * 4096
+                                * getattr(props, "clock_rate", 0) * 1e3 / 1e12}
 
     if not args.no_cpu_baseline:
         import oracle
