@@ -185,11 +185,23 @@ def main() -> int:
     }
     # the published peak next to what this board's CU count and maximum engine clock give
     props = torch.cuda.get_device_properties(0)
+    clock_mhz = 0.0
+    try:    # rocminfo lists every agent; the GPU agents are the ones with a gfx name
+        import re
+        import subprocess
+        txt = subprocess.run(["rocminfo"], capture_output=True, text=True, timeout=60).stdout
+        for agent in txt.split("*******")[1:]:
+            if re.search(r"Name:\s+gfx9", agent):
+                m = re.search(r"Max Clock Freq\. \(MHz\):\s+(\d+)", agent)
+                if m:
+                    clock_mhz = float(m.group(1))
+                    break
+    except Exception:
+        pass
     out["roofline"]["peak_source"] = "published MI355X dense bf16 MFMA figure (256 CUs x 4096 flop/clk x 2.4 GHz)"
     out["roofline"]["board"] = {"name": props.name, "cus": props.multi_processor_count,
-                                "max_engine_clock_mhz": getattr(props, "clock_rate", 0) / 1e3,
-                                "derived_peak_tflops": props.multi_processor_count * 4096
-                                * getattr(props, "clock_rate", 0) * 1e3 / 1e12}
+                                "max_engine_clock_mhz": clock_mhz,
+                                "derived_peak_tflops": props.multi_processor_count * 4096 * clock_mhz * 1e6 / 1e12}
 
     if not args.no_cpu_baseline:
         import oracle

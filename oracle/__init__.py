@@ -16,6 +16,10 @@ Stages (one attention head at a time, arrays are float32 ``[N][d]``):
                       Attention Computation"), ``softmax_rows`` Alg. 2's first step,
                       ``build_mask_global`` Alg. 2 over the flattened map: the pattern
                       construction as the paper prints it
+* ``js_distance``, ``last_row_estimate``, ``determine_pattern``
+                      Alg. 3 (Determine Sparse Pattern): the last query block's
+                      block-averaged attention estimate, its Jensen-Shannon distances to
+                      the uniform distribution and to the pivot's representative, the gate
 * ``prefill_layer``   Alg. 1 / Alg. 4 for one layer with given pivots: pivots run
                       dense, their score map becomes the cluster's pattern, all
                       other heads of the cluster run masked attention with it.
@@ -67,6 +71,8 @@ def _load():
         L.spo_build_mask_global.restype = ctypes.c_int
         L.spo_build_mask_global.argtypes = [fp, ctypes.c_int, ctypes.c_float, ctypes.c_int, ip, ip,
                                             ctypes.POINTER(ctypes.c_int64)]
+        L.spo_js_distance.restype = ctypes.c_int
+        L.spo_js_distance.argtypes = [fp, fp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
 
@@ -206,9 +212,36 @@ def build_mask_global(scores, gamma: float, forced: bool = True):
     return idx, cnt, int(K.value)
 
 
+def js_distance(p, q) -> float:
+    """sqrt of the Jensen-Shannon divergence (natural log) of two non-negative vectors."""
+    p, pp = _f(p)
+    q, qp = _f(q)
+    assert p.shape == q.shape and p.ndim == 1
+    out = ctypes.c_double(0.0)
+    rc = _load().spo_js_distance(pp, qp, p.shape[0], ctypes.byref(out))
+    if rc:
+        raise ValueError(f"spo_js_distance failed ({rc})")
+    return float(out.value)
+
+
+def last_row_estimate(q, k, block: int, scale: Optional[float] = None):
+    """a_hat of Alg. 3: softmax over key blocks of the pooled scaled logits of the last query block."""
+    nkb = q.shape[0] // block
+    return softmax_rows(mean_logit_rows(q, k, block, rows=[nkb - 1], scale=scale))[0]
+
+
+def determine_pattern(a_hat, a_tilde, delta: float, tau: float):
+    """Alg. 3's gate.  a_tilde None: no pivotal representative exists yet, only the sparsity test applies.
+    Returns (shared: bool, d_sparse, d_sim)."""
+    n = len(a_hat)
+    d_sparse = js_distance(a_hat, np.full(n, 1.0 / n, dtype=np.float32))
+    d_sim = 0.0 if a_tilde is None else js_distance(a_hat, a_tilde)
+    return (d_sparse < delta) and (d_sim < tau), d_sparse, d_sim
+
+
 def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: float,
                   rows: Optional[Sequence[int]] = None, scale: Optional[float] = None,
-                  masks=None, paper_pattern: bool = False):
+                  masks=None, paper_pattern: bool = False, gate=None, shared=None):
     """One layer of pattern sharing with given pivots (Alg. 1 / Alg. 2 / Alg. 4).
 
     q [N][Hq][d], k/v [N][Hkv][d] float32.  Returns a dict with
@@ -220,7 +253,11 @@ def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: floa
     to check outputs against a pattern produced elsewhere).  `paper_pattern` swaps
     the pattern construction for the paper's printed one (row softmax of block-mean
     logits, one selection over the flattened map, forced sink/diagonal kept); it
-    needs every row unless `masks` is given."""
+    needs every row unless `masks` is given.  `gate` = (delta, tau) applies Alg. 3 to
+    every clustered non-pivot head, the pivot's own estimate serving as the pivotal
+    representative: heads that fail run dense (the stand-in for the fallback pattern);
+    the result then also holds "shared" [Hq] bool and "dist" [Hq][2].  `shared`, if
+    given, replaces the gate's decisions (to check outputs under decisions taken elsewhere)."""
     q = np.asarray(q, dtype=np.float32)
     k = np.asarray(k, dtype=np.float32)
     v = np.asarray(v, dtype=np.float32)
@@ -253,13 +290,27 @@ def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: floa
     if masks is not None:
         kb_idx, kb_cnt = masks
     pivots = {int(p) for p in pivot_heads}
+    decided = np.ones(Hq, dtype=bool)
+    dist = np.zeros((Hq, 2), dtype=np.float64)
+    if gate is not None:
+        est = {}
+        for h in range(Hq):
+            if int(head_to_cluster[h]) >= 0:
+                est[h] = last_row_estimate(q[:, h], k[:, h // G], block, scale)
+        for h in range(Hq):
+            c = int(head_to_cluster[h])
+            if c < 0:
+                continue
+            decided[h], dist[h, 0], dist[h, 1] = determine_pattern(est[h], est[int(pivot_heads[c])], gate[0], gate[1])
+    if shared is not None:
+        decided = np.asarray(shared, dtype=bool)
     for h in range(Hq):
         if h in pivots:
             continue
         c = int(head_to_cluster[h])
         g = h // G
-        if c < 0:
+        if c < 0 or not decided[h]:
             o[:, h], _, _ = dense_rows(q[:, h], k[:, g], v[:, g], block, rows, scale, want_scores=False)
         else:
             o[:, h] = masked_rows(q[:, h], k[:, g], v[:, g], block, kb_idx[c], kb_cnt[c], rows, scale)
-    return {"o": o, "scores": scores, "kb_idx": kb_idx, "kb_cnt": kb_cnt}
+    return {"o": o, "scores": scores, "kb_idx": kb_idx, "kb_cnt": kb_cnt, "shared": decided, "dist": dist}

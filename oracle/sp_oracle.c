@@ -426,3 +426,29 @@ int spo_build_mask_global(const float *scores, int nkb, float gamma, int forced,
   free(on);
   return 0;
 }
+
+/* ==== Determine Sparse Pattern (Alg. 3) =====================================
+ *
+ *   a_hat    the block-averaged attention estimate of the last query block:
+ *            softmax over key blocks of the pooled, scaled logits of the last
+ *            B queries -- i.e. row nkb-1 of the map spo_mean_logit_rows /
+ *            spo_softmax_rows give (the caller composes those two).
+ *   distance sqrt(JSD(p || q)), JSD(p||q) = KL(p||m)/2 + KL(q||m)/2 with
+ *            m = (p+q)/2, natural logarithm, 0*log(0) = 0.
+ *   decision shared_pivot iff d(a_hat, uniform) < delta and
+ *            d(a_hat, a_tilde) < tau; otherwise the fallback pattern.
+ */
+int spo_js_distance(const float *p, const float *q, int n, double *out) {
+  if (n <= 0 || !p || !q || !out) return 1;
+  double a = 0.0, b = 0.0;
+  for (int j = 0; j < n; ++j) {
+    const double pj = p[j], qj = q[j];
+    if (pj < 0.0 || qj < 0.0) return 1;
+    const double m = 0.5 * (pj + qj);
+    if (pj > 0.0) a += pj * log(pj / m);
+    if (qj > 0.0) b += qj * log(qj / m);
+  }
+  const double jsd = 0.5 * a + 0.5 * b;
+  *out = sqrt(jsd > 0.0 ? jsd : 0.0);
+  return 0;
+}
