@@ -46,6 +46,8 @@ def main() -> int:
                     help="pivot score map: exact block mass (default) or the paper's row softmax of block-mean logits")
     ap.add_argument("--select-mode", choices=["row", "global"], default="row",
                     help="Alg. 2 per query-block row (default) or once over the flattened map as printed")
+    ap.add_argument("--gate", default=None, metavar="DELTA,TAU",
+                    help="run Alg. 3's gate in front of the sharing (sp_prefill_layer_gated), e.g. 0.3,0.2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-all", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -83,8 +85,18 @@ def main() -> int:
     select_mode = sp.SP_SELECT_GLOBAL if args.select_mode == "global" else sp.SP_SELECT_PER_ROW
     default_modes = args.score_mode == "mass" and args.select_mode == "row"
 
+    gate = None
+    if args.gate:
+        gate = tuple(float(x) for x in args.gate.split(","))
+        a_hat = torch.empty((1, Hq, nqb), dtype=torch.float32, device="cuda")
+        dist = torch.empty((1, Hq, 2), dtype=torch.float32, device="cuda")
+        pattern = torch.empty((1, Hq), dtype=torch.int32, device="cuda")
+
     def step():
-        if default_modes:
+        if gate:
+            sp.sp_prefill_layer_gated(shape, q, k, v, h2c, piv, cfg.gamma, gate[0], gate[1], score_mode, select_mode,
+                                      o, scores, kb_idx, kb_cnt, a_hat, dist, pattern, ws)
+        elif default_modes:
             sp.sp_prefill_layer(shape, q, k, v, h2c, piv, cfg.gamma, o, scores, kb_idx, kb_cnt, ws)
         else:
             sp.sp_prefill_layer_modes(shape, q, k, v, h2c, piv, cfg.gamma, score_mode, select_mode, o, scores,
@@ -117,11 +129,16 @@ def main() -> int:
     # work actually done
     cnt = kb_cnt.cpu().numpy()[0].astype(np.int64)            # [C][nqb]
     tile_flops = 4.0 * B * B * d
-    n_sparse_heads = sum(1 for h in range(Hq) if h2c[h] >= 0 and h not in piv)
     n_free = sum(1 for h in range(Hq) if h2c[h] < 0)
+    fell_back = []          # clustered heads the gate sent to the dense fallback
+    if gate:
+        pat_h = pattern.cpu().numpy()[0]
+        fell_back = [h for h in range(Hq) if h2c[h] >= 0 and h not in piv and pat_h[h] < 0]
     dense_tiles_per_head = nqb * (nqb + 1) // 2
     pivot_tiles = (C + n_free) * dense_tiles_per_head
-    sparse_tiles = int(sum(cnt[h2c[h]].sum() for h in range(Hq) if h2c[h] >= 0 and h not in piv))
+    sparse_tiles = int(sum(cnt[h2c[h]].sum() for h in range(Hq)
+                           if h2c[h] >= 0 and h not in piv and h not in fell_back))
+    sparse_tiles += len(fell_back) * dense_tiles_per_head
     density = float(cnt.sum() / (C * dense_tiles_per_head))
     dense_equiv_flops = Hq * 4.0 * d * (N * (N + 1) / 2.0)    # exact causal pair count
     computed_flops = (pivot_tiles + sparse_tiles) * tile_flops
@@ -165,7 +182,8 @@ def main() -> int:
                    "seed": L["seed"], "density": density},
         "ms_per_layer": ms_step,
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
-        "pattern": {"score_mode": args.score_mode, "select_mode": args.select_mode},
+        "pattern": {"score_mode": args.score_mode, "select_mode": args.select_mode,
+                    "gate": None if not gate else {"delta": gate[0], "tau": gate[1], "heads_fallen_back": len(fell_back)}},
         "computed_tflops": computed_flops / (ms_step * 1e-3) / 1e12,
         "computed_frac_of_bf16_peak": computed_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "tiles": {"pivot": int(pivot_tiles), "sparse": int(sparse_tiles),

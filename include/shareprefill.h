@@ -72,14 +72,15 @@ sp_status sp_profile_read(float *ms, int32_t *launches, int32_t reset);
 
 /*
  * Bytes of device workspace that suffice for any of the attention calls below
- * (sp_dense_attn_with_block_scores, sp_block_sparse_attn, sp_prefill_layer,
- * sp_prefill_layer_modes in every mode) for this shape when at most `n_dense_heads`
+ * (sp_dense_attn_with_block_scores, sp_block_sparse_attn, sp_block_sparse_attn_gated,
+ * sp_prefill_layer, sp_prefill_layer_modes and sp_prefill_layer_gated in every mode)
+ * for this shape when at most `n_dense_heads`
  * heads per batch entry produce a block score map in one call (0 if no scores are
  * ever requested).
  */
 sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_t *bytes);
 
-/* Workspace of sp_block_mean_logit_scores for n_heads listed heads. */
+/* Workspace of sp_block_mean_logit_scores and of sp_determine_pattern for n_heads listed heads. */
 sp_status sp_score_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *bytes);
 
 /* Workspace of sp_build_block_mask_global for n_maps maps of nqb x nqb blocks. */
@@ -168,6 +169,44 @@ sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, 
                                      int32_t forced, int32_t *kb_idx, int32_t *kb_cnt, void *workspace,
                                      size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Alg. 3 (Determine Sparse Pattern) for the listed heads.  For each listed head n:
+ *   a_hat[n]  = softmax over key blocks of the pooled, scaled logits of the last `block`
+ *               queries against every key block (causal inside the last block), i.e. row
+ *               nqb-1 of the map sp_block_mean_logit_scores gives;
+ *   d_sparse  = sqrt(JSD(a_hat[n] || uniform over the nkb key blocks)),
+ *   d_sim     = sqrt(JSD(a_hat[n] || a_hat[ref_pos[n]])), 0 when ref_pos[n] < 0 (no pivotal
+ *               representative exists yet); JSD with the natural logarithm, summed in fp64;
+ *   the head shares its pivot's pattern iff d_sparse < delta and d_sim < tau (both strict).
+ *   head_ids     host [n_heads] distinct query heads
+ *   ref_pos      host [n_heads] position in head_ids of the head whose estimate serves as the
+ *                pivotal representative a~ (the cluster's pivot; a head may name itself), or -1
+ *   shared_map   host [n_heads] value stored for a head that passes (its cluster's list index)
+ *   a_hat        device fp32 [batch][n_heads][nkb]        (output)
+ *   dist         device fp32 [batch][n_heads][2]          (output: d_sparse, d_sim)
+ *   head_pattern device int32 [batch][n_q_heads]          (output, indexed by query-head id; only
+ *                the listed heads' entries are written: shared_map[n] if the head passes, else -1)
+ *   workspace    sp_score_workspace_bytes(shape, n_heads)
+ * The paper sends failing heads to the vertical-slash search (Alg. 5); in this library a head
+ * whose entry is negative runs dense attention.
+ */
+sp_status sp_determine_pattern(const sp_shape *shape, const void *q, const void *k, const int32_t *head_ids,
+                               int32_t n_heads, const int32_t *ref_pos, const int32_t *shared_map, float delta,
+                               float tau, float *a_hat, float *dist, int32_t *head_pattern, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
+
+/*
+ * sp_block_sparse_attn with the list of each head chosen on the device: listed head h of batch
+ * entry b uses list head_pattern[b][h] (clamped to n_maps-1), or, if that entry is negative,
+ * attends to every key block 0..i (dense causal attention).  head_pattern is the array
+ * sp_determine_pattern writes, read by the kernel when it runs: no host round trip.
+ *   head_pattern device int32 [batch][n_q_heads]
+ */
+sp_status sp_block_sparse_attn_gated(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                     const int32_t *head_ids, int32_t n_heads, const int32_t *kb_idx,
+                                     const int32_t *kb_cnt, int32_t n_maps, const int32_t *head_pattern, void *o,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* How the pivot's block score map is formed / how Alg. 2 turns it into a pattern. */
 enum { SP_SCORE_BLOCK_MASS = 0,   /* exact attention mass per block (sp_dense_attn_with_block_scores) */
        SP_SCORE_MEAN_LOGIT = 1 }; /* row softmax of block-mean logits (sp_block_mean_logit_scores) */
@@ -202,6 +241,23 @@ sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const voi
                                  float gamma, int32_t score_mode, int32_t select_mode, void *o, float *block_scores,
                                  int32_t *kb_idx, int32_t *kb_cnt, void *workspace, size_t workspace_bytes,
                                  void *hip_stream);
+
+/*
+ * sp_prefill_layer_modes preceded by Alg. 3's gate (Alg. 1 with Alg. 3, Alg. 4 and Alg. 2):
+ * every head's estimate a_hat is formed, the pivot's own serving as its cluster's representative
+ * a~; a clustered non-pivot head shares its cluster's pattern iff d_sparse < delta and
+ * d_sim < tau, and otherwise runs dense (the stand-in for the vertical-slash fallback).  Pivots
+ * and heads outside every cluster run dense whatever their distances are.
+ *   a_hat        device fp32 [batch][n_q_heads][nkb]   (output)
+ *   dist         device fp32 [batch][n_q_heads][2]     (output)
+ *   head_pattern device int32 [batch][n_q_heads]       (output: cluster id if shared, else -1)
+ * One stream, no host synchronisation: the sparse kernel reads head_pattern on the device.
+ */
+sp_status sp_prefill_layer_gated(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                 const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                                 float gamma, float delta, float tau, int32_t score_mode, int32_t select_mode, void *o,
+                                 float *block_scores, int32_t *kb_idx, int32_t *kb_cnt, float *a_hat, float *dist,
+                                 int32_t *head_pattern, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,7 @@ EXPORTED_SYMBOLS = [
     "sp_block_sparse_attn", "sp_prefill_layer",
     "sp_score_workspace_bytes", "sp_mask_workspace_bytes", "sp_block_mean_logit_scores",
     "sp_build_block_mask_global", "sp_prefill_layer_modes",
+    "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated",
 ]
 
 SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT = 0, 1
@@ -89,6 +90,16 @@ def lib() -> ctypes.CDLL:
         L.sp_prefill_layer_modes.restype = ctypes.c_int
         L.sp_prefill_layer_modes.argtypes = [sp, vp, vp, vp, ip, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_int32,
                                              ctypes.c_int32, vp, fp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.sp_determine_pattern.restype = ctypes.c_int
+        L.sp_determine_pattern.argtypes = [sp, vp, vp, ip, ctypes.c_int32, ip, ip, ctypes.c_float, ctypes.c_float,
+                                           fp, fp, vp, vp, ctypes.c_size_t, vp]
+        L.sp_block_sparse_attn_gated.restype = ctypes.c_int
+        L.sp_block_sparse_attn_gated.argtypes = [sp, vp, vp, vp, ip, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp,
+                                                 vp, ctypes.c_size_t, vp]
+        L.sp_prefill_layer_gated.restype = ctypes.c_int
+        L.sp_prefill_layer_gated.argtypes = [sp, vp, vp, vp, ip, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
+                                             ctypes.c_float, ctypes.c_int32, ctypes.c_int32, vp, fp, vp, vp, fp, fp,
+                                             vp, vp, ctypes.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -212,3 +223,29 @@ def sp_prefill_layer_modes(shape: SpShape, q, k, v, head_to_cluster, pivot_heads
         ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_to_cluster), _ids(pivot_heads),
         len(pivot_heads), ctypes.c_float(gamma), int(score_mode), int(select_mode), _ptr(o), _ptr(block_scores),
         _ptr(kb_idx), _ptr(kb_cnt), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def sp_determine_pattern(shape: SpShape, q, k, head_ids, ref_pos, shared_map, delta: float, tau: float, a_hat, dist,
+                         head_pattern, workspace):
+    assert len(head_ids) == len(ref_pos) == len(shared_map)
+    _check(lib().sp_determine_pattern(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ids(head_ids), len(head_ids), _ids(ref_pos), _ids(shared_map),
+        ctypes.c_float(delta), ctypes.c_float(tau), _ptr(a_hat), _ptr(dist), _ptr(head_pattern), _ptr(workspace),
+        _nbytes(workspace), _stream()))
+
+
+def sp_block_sparse_attn_gated(shape: SpShape, q, k, v, head_ids, kb_idx, kb_cnt, n_maps: int, head_pattern, o,
+                               workspace):
+    _check(lib().sp_block_sparse_attn_gated(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_ids), len(head_ids), _ptr(kb_idx), _ptr(kb_cnt),
+        n_maps, _ptr(head_pattern), _ptr(o), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def sp_prefill_layer_gated(shape: SpShape, q, k, v, head_to_cluster, pivot_heads, gamma: float, delta: float,
+                           tau: float, score_mode: int, select_mode: int, o, block_scores, kb_idx, kb_cnt, a_hat,
+                           dist, head_pattern, workspace):
+    _check(lib().sp_prefill_layer_gated(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_to_cluster), _ids(pivot_heads),
+        len(pivot_heads), ctypes.c_float(gamma), ctypes.c_float(delta), ctypes.c_float(tau), int(score_mode),
+        int(select_mode), _ptr(o), _ptr(block_scores), _ptr(kb_idx), _ptr(kb_cnt), _ptr(a_hat), _ptr(dist),
+        _ptr(head_pattern), _ptr(workspace), _nbytes(workspace), _stream()))

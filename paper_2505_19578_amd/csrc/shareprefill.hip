@@ -12,7 +12,7 @@
 //                    DENSE=false walks a per-row key-block index list (Sec. 5.1 A(Q,K,V,M)).
 //   mask_kernel      Alg. 2 per query-block row in exact integer arithmetic, one wavefront
 //                    per row: threshold search + ballot/popcount prefix sums.
-//   block_pool_kernel, mean_logit_softmax_kernel, gsel_*_kernel
+//   key_pool_kernel, query_pool_kernel, mean_logit_softmax_kernel, gsel_*_kernel
 //                    the pattern construction as the paper prints it: row softmax of the
 //                    block-mean QK logits (Sec. 5.2) and Alg. 2 over the flattened map.
 //
@@ -159,6 +159,10 @@ struct AttnParams {
   float *scores;  // dense: [b][n][nqb][nkb], or null
   const int32_t *kb_idx;  // sparse: [b][n_maps][nqb][nkb]
   const int32_t *kb_cnt;  // sparse: [b][n_maps][nqb]
+  // sparse, optional: per (batch entry, query head) pattern chosen on the device (Alg. 3's gate):
+  // a list index in [0, n_maps), or < 0 = no shared pattern, the head walks every key block 0..i
+  const int32_t *head_pattern;  // [b][n_q_heads]
+  int n_q_heads;
   int32_t head_ids[SP_MAX_SLOTS];  // query head of each slot, -1 = padding slot
   int32_t head_map[SP_MAX_SLOTS];  // sparse: which list the slot's head uses
   int32_t head_pos[SP_MAX_SLOTS];  // position of the head in the caller's list (scores / lws index)
@@ -276,10 +280,19 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   if (DENSE) {
     nblk = i + 1;
   } else {
-    const int64_t lrow_id = ((int64_t)b * p.n_maps + p.head_map[slot]) * p.nqb + i;
-    nblk = p.kb_cnt[lrow_id];
-    nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
-    list = p.kb_idx + lrow_id * nkb;
+    int map = p.head_map[slot];
+    if (p.head_pattern) {
+      map = __builtin_amdgcn_readfirstlane(p.head_pattern[(int64_t)b * p.n_q_heads + head]);
+      map = map >= p.n_maps ? p.n_maps - 1 : map;
+    }
+    if (map < 0) {
+      nblk = i + 1;  // list stays null: dense walk
+    } else {
+      const int64_t lrow_id = ((int64_t)b * p.n_maps + map) * p.nqb + i;
+      nblk = p.kb_cnt[lrow_id];
+      nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
+      list = p.kb_idx + lrow_id * nkb;
+    }
   }
   const int nsub = nblk * SPB;
   const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
@@ -290,7 +303,7 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   // whatever the list holds)
   auto block_of = [&](int t) -> int {
     int e = (t < nsub ? t : nsub - 1) / SPB;
-    if (DENSE) return e;
+    if (DENSE || list == nullptr) return e;
     const int j = list[e];
     return j < 0 ? 0 : (j > i ? i : j);
   };
@@ -524,7 +537,7 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   if (nsub > 0) {
     // leading run of sub-tiles that lie before the first diagonal entry of the list
     int nfast;
-    if (DENSE) {
+    if (DENSE || list == nullptr) {
       nfast = i * SPB;
     } else {
       int first = nblk;
@@ -732,19 +745,34 @@ __device__ __forceinline__ float bf16_bits_to_float(uint16_t x) { return __uint_
 struct PoolParams {
   const uint16_t *q, *k;
   int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
-  int nqb, group, n_heads;
-  float *qsum;   // [b][n][nqb][D]   sum of the block's queries
-  float *ksumT;  // [b][n][D][nqb]   sum of the block's keys, block index fastest
-  float *diag;   // [b][n][nqb]      sum over the diagonal block's causal entries of q_t . k_s
+  int nqb, group, n_heads, n_kv_heads;
+  int row0, n_rows;  // query-block rows row0 .. row0 + n_rows - 1 are wanted
+  float *qsum;       // [b][n][n_rows][D]   sum of the block's queries
+  float *ksumT;      // [b][kvh][D][nqb]    sum of the block's keys, block index fastest
+  float *diag;       // [b][n][n_rows]      sum over the diagonal block's causal entries of q_t . k_s
+  float *out;        // [b][n][n_rows][nqb] row softmax of the block-mean logits
+  float c_full, c_diag;
   int32_t head_ids[SP_MAX_HEADS];
 };
 
 // The average of q_t . k_s over a full block is (sum_t q_t) . (sum_s k_s) / B^2, so the block-mean
-// logits need only per-block sums of Q and K.  The diagonal block keeps s <= t only:
-// sum_t q_t . (sum_{s<=t} k_s), a running key sum walked once.  One thread per head dimension.
+// logits need only per-block sums of Q and K.  One thread per head dimension, one block per workgroup.
 template <int D, int B>
-__global__ __launch_bounds__(D) void block_pool_kernel(PoolParams p) {
-  const int i = blockIdx.x, n = blockIdx.y, b = blockIdx.z, e = threadIdx.x;
+__global__ __launch_bounds__(D) void key_pool_kernel(PoolParams p) {
+  const int i = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z, e = threadIdx.x;
+  const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)i * B * p.k_st + (int64_t)kvh * p.k_sh + e;
+  float run = 0.f;
+#pragma unroll 8
+  for (int t = 0; t < B; ++t) run += bf16_bits_to_float(kp[(int64_t)t * p.k_st]);
+  p.ksumT[(((int64_t)b * p.n_kv_heads + kvh) * D + e) * p.nqb + i] = run;
+}
+
+// Query sums of the wanted rows and, for the diagonal block (which keeps s <= t only), the sum
+// sum_t q_t . (sum_{s<=t} k_s) from a running key sum walked once.
+template <int D, int B>
+__global__ __launch_bounds__(D) void query_pool_kernel(PoolParams p) {
+  const int r = blockIdx.x, n = blockIdx.y, b = blockIdx.z, e = threadIdx.x;
+  const int i = p.row0 + r;
   const int head = p.head_ids[n];
   const uint16_t *qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * B * p.q_st + (int64_t)head * p.q_sh + e;
   const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)i * B * p.k_st + (int64_t)(head / p.group) * p.k_sh + e;
@@ -757,13 +785,12 @@ __global__ __launch_bounds__(D) void block_pool_kernel(PoolParams p) {
     qs += qq;
     acc = fmaf(qq, run, acc);
   }
-  const int64_t hb = (int64_t)b * p.n_heads + n;
-  p.qsum[(hb * p.nqb + i) * D + e] = qs;
-  p.ksumT[(hb * D + e) * p.nqb + i] = run;
+  const int64_t hr = ((int64_t)b * p.n_heads + n) * p.n_rows + r;
+  p.qsum[hr * D + e] = qs;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
   if constexpr (D == 64) {
-    if (e == 0) p.diag[hb * p.nqb + i] = acc;
+    if (e == 0) p.diag[hr] = acc;
   } else {
     __shared__ float part[D / 64];
     if ((e & 63) == 0) part[e >> 6] = acc;
@@ -772,32 +799,32 @@ __global__ __launch_bounds__(D) void block_pool_kernel(PoolParams p) {
       float s = 0.f;
 #pragma unroll
       for (int w = 0; w < D / 64; ++w) s += part[w];
-      p.diag[hb * p.nqb + i] = s;
+      p.diag[hr] = s;
     }
   }
 }
 
 // Four query-block rows per workgroup: thread j forms the four pooled dot products against key block j
 // (block index fastest in ksumT, so the loads coalesce), then one wavefront per row applies the row
-// softmax in place (Alg. 2, first step).  Entries beyond the diagonal are written as 0.
+// softmax in place (Alg. 2, first step; Alg. 3's estimate when only the last row is asked for).
+// Entries beyond the diagonal are written as 0.
 template <int D>
-__global__ __launch_bounds__(256) void mean_logit_softmax_kernel(const float *__restrict__ qsum,
-                                                                 const float *__restrict__ ksumT,
-                                                                 const float *__restrict__ diag,
-                                                                 float *__restrict__ scores, int nqb,
-                                                                 float c_full, float c_diag) {
+__global__ __launch_bounds__(256) void mean_logit_softmax_kernel(PoolParams p) {
   constexpr int R = 4;
   __shared__ float qs[R][D];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int i0 = blockIdx.x * R;
+  const int r0 = blockIdx.x * R;
   const int64_t hb = blockIdx.y;
+  const int b = (int)(hb / p.n_heads), n = (int)(hb % p.n_heads);
+  const int nqb = p.nqb;
   for (int x = tid; x < R * D; x += 256) {
     const int r = x / D, e = x % D;
-    qs[r][e] = (i0 + r < nqb) ? qsum[(hb * nqb + i0 + r) * D + e] : 0.f;
+    qs[r][e] = (r0 + r < p.n_rows) ? p.qsum[((hb * p.n_rows) + r0 + r) * D + e] : 0.f;
   }
   __syncthreads();
-  const float *kT = ksumT + hb * D * nqb;
-  const int imax = min(i0 + R - 1, nqb - 1);
+  const float *kT = p.ksumT + ((int64_t)b * p.n_kv_heads + p.head_ids[n] / p.group) * D * nqb;
+  const int rmax = min(r0 + R - 1, p.n_rows - 1);
+  const int imax = p.row0 + rmax;
   for (int j = tid; j <= imax; j += 256) {
     float acc[R] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
@@ -808,15 +835,15 @@ __global__ __launch_bounds__(256) void mean_logit_softmax_kernel(const float *__
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const int i = i0 + r;
-      if (i < nqb && j <= i)
-        scores[(hb * nqb + i) * nqb + j] = (j < i) ? acc[r] * c_full : diag[hb * nqb + i] * c_diag;
+      const int i = p.row0 + r0 + r;
+      if (r0 + r < p.n_rows && j <= i)
+        p.out[(hb * p.n_rows + r0 + r) * nqb + j] = (j < i) ? acc[r] * p.c_full : p.diag[hb * p.n_rows + r0 + r] * p.c_diag;
     }
   }
   __syncthreads();
-  const int i = i0 + w;
-  if (i >= nqb) return;
-  float *row = scores + (hb * nqb + i) * nqb;
+  if (r0 + w >= p.n_rows) return;
+  const int i = p.row0 + r0 + w;
+  float *row = p.out + (hb * p.n_rows + r0 + w) * nqb;
   float mx = -INFINITY;
   for (int j = lane; j <= i; j += 64) mx = fmaxf(mx, row[j]);
 #pragma unroll
@@ -826,6 +853,63 @@ __global__ __launch_bounds__(256) void mean_logit_softmax_kernel(const float *__
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off, 64);
   for (int j = lane; j < nqb; j += 64) row[j] = (j <= i) ? expf(row[j] - mx) / den : 0.f;
+}
+
+// ---- Alg. 3 (Determine Sparse Pattern): Jensen-Shannon gate ------------------------------------
+struct GateParams {
+  const float *a_hat;     // [b][n][nkb] estimates of the listed heads
+  float *dist;            // [b][n][2]   d_sparse, d_sim
+  int32_t *head_pattern;  // [b][n_q_heads], entry of each listed head written
+  int nkb, n_heads, n_q_heads;
+  float delta, tau;
+  int32_t head_ids[SP_MAX_HEADS];
+  int32_t ref_pos[SP_MAX_HEADS];     // position of the head whose estimate is the representative, or -1
+  int32_t shared_map[SP_MAX_HEADS];  // value written when the pattern is shared
+};
+
+// sqrt(JSD) of the head's estimate against the uniform distribution and against its representative,
+// natural logarithm, accumulated in fp64 (every per-entry contribution is non-negative); one
+// workgroup per (head, batch entry).
+__global__ __launch_bounds__(256) void js_gate_kernel(GateParams p) {
+  __shared__ double red[2][4];
+  const int n = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const float *a = p.a_hat + ((int64_t)b * p.n_heads + n) * p.nkb;
+  const int rp = p.ref_pos[n];
+  const float *ref = (rp >= 0) ? p.a_hat + ((int64_t)b * p.n_heads + rp) * p.nkb : nullptr;
+  const double u = 1.0 / (double)p.nkb;
+  auto term = [](double x, double y) -> double {  // x ln(x/m) + y ln(y/m), m = (x+y)/2
+    const double m = 0.5 * (x + y);
+    double t = 0.0;
+    if (x > 0.0) t += x * log(x / m);
+    if (y > 0.0) t += y * log(y / m);
+    return t;
+  };
+  double su = 0.0, sr = 0.0;
+  for (int j = tid; j < p.nkb; j += 256) {
+    const double x = (double)a[j];
+    su += term(x, u);
+    if (ref) sr += term(x, (double)ref[j]);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    su += __shfl_xor(su, off, 64);
+    sr += __shfl_xor(sr, off, 64);
+  }
+  if (lane == 0) {
+    red[0][w] = su;
+    red[1][w] = sr;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const double ju = 0.5 * (red[0][0] + red[0][1] + red[0][2] + red[0][3]);
+    const double jr = 0.5 * (red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+    const double d_sparse = sqrt(ju > 0.0 ? ju : 0.0), d_sim = sqrt(jr > 0.0 ? jr : 0.0);
+    const int64_t hb = (int64_t)b * p.n_heads + n;
+    p.dist[hb * 2] = (float)d_sparse;
+    p.dist[hb * 2 + 1] = (float)d_sim;
+    const bool shared = d_sparse < (double)p.delta && d_sim < (double)p.tau;
+    p.head_pattern[(int64_t)b * p.n_q_heads + p.head_ids[n]] = shared ? p.shared_map[n] : -1;
+  }
 }
 
 // ---- Alg. 2 over the flattened map, exact integers -------------------------------------------
@@ -1108,17 +1192,17 @@ size_t lws_bytes(const sp_shape *s, int n_dense) {
   return align_up((size_t)s->batch * n_dense * nqb * nqb * s->block * sizeof(float), 256);
 }
 
-// scratch of the paper-literal pattern construction for n heads (= maps) per batch entry:
-// [qsum | ksumT | diag | per-map selection scratch]
+// scratch of the pooled score path for n listed heads per batch entry and of the global selection
+// for n maps per batch entry: [ksumT | qsum | diag | per-map selection scratch]
 struct PatternLayout {
-  size_t qsum, ksumT, diag, gsel, total;
+  size_t ksumT, qsum, diag, gsel, total;
 };
 PatternLayout pattern_layout(const sp_shape *s, int n) {
   const size_t nqb = s->seq / s->block, maps = (size_t)s->batch * n;
   PatternLayout L;
-  L.qsum = 0;
-  L.ksumT = L.qsum + align_up(maps * nqb * s->head_dim * sizeof(float), 256);
-  L.diag = L.ksumT + align_up(maps * nqb * s->head_dim * sizeof(float), 256);
+  L.ksumT = 0;
+  L.qsum = L.ksumT + align_up((size_t)s->batch * s->n_kv_heads * nqb * s->head_dim * sizeof(float), 256);
+  L.diag = L.qsum + align_up(maps * nqb * s->head_dim * sizeof(float), 256);
   L.gsel = L.diag + align_up(maps * nqb * sizeof(float), 256);
   L.total = L.gsel + align_up(maps * gsel_map_bytes((int)nqb), 256);
   return L;
@@ -1277,9 +1361,10 @@ sp_status launch_mask(const float *scores, int n_maps, int nqb, int nkb, float g
   return hip_check(hipGetLastError(), "mask_kernel launch");
 }
 
-// row softmax of the block-mean logits of the listed heads into scores[b][n][nqb][nkb]
+// row softmax of the block-mean logits of the listed heads, query-block rows row0 .. row0+n_rows-1,
+// into out[b][n][n_rows][nkb]
 sp_status launch_mean_logit_scores(const sp_shape *s, const void *q, const void *k, const int32_t *heads, int n,
-                                   float *scores, char *pattern_ws, hipStream_t st) {
+                                   int row0, int n_rows, float *out, char *pattern_ws, hipStream_t st) {
   if ((int64_t)s->batch * n > 65535) {
     set_err("batch * heads = %lld exceeds 65535", (long long)s->batch * n);
     return SP_ERR_UNSUPPORTED;
@@ -1299,16 +1384,26 @@ sp_status launch_mean_logit_scores(const sp_shape *s, const void *q, const void 
   pp.nqb = nqb;
   pp.group = s->n_q_heads / s->n_kv_heads;
   pp.n_heads = n;
-  pp.qsum = (float *)(pattern_ws + L.qsum);
+  pp.n_kv_heads = s->n_kv_heads;
+  pp.row0 = row0;
+  pp.n_rows = n_rows;
   pp.ksumT = (float *)(pattern_ws + L.ksumT);
+  pp.qsum = (float *)(pattern_ws + L.qsum);
   pp.diag = (float *)(pattern_ws + L.diag);
+  pp.out = out;
   for (int a = 0; a < n; ++a) pp.head_ids[a] = heads[a];
   const float scale = (s->softmax_scale > 0.f) ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
   const float B = (float)s->block;
-  const float c_full = scale / (B * B), c_diag = scale / (B * (B + 1.f) * 0.5f);
+  pp.c_full = scale / (B * B);
+  pp.c_diag = scale / (B * (B + 1.f) * 0.5f);
   ProfScope prof(KK_SCORE, st);
-  dim3 gpool(nqb, n, s->batch), glog((nqb + 3) / 4, s->batch * n);
-#define SP_POOL(D_, B_) hipLaunchKernelGGL((block_pool_kernel<D_, B_>), gpool, dim3(D_), 0, st, pp)
+  dim3 gk(nqb, s->n_kv_heads, s->batch), gq(n_rows, n, s->batch), glog((n_rows + 3) / 4, s->batch * n);
+#define SP_POOL(D_, B_)                                                              \
+  do {                                                                               \
+    hipLaunchKernelGGL((key_pool_kernel<D_, B_>), gk, dim3(D_), 0, st, pp);          \
+    hipLaunchKernelGGL((query_pool_kernel<D_, B_>), gq, dim3(D_), 0, st, pp);        \
+    hipLaunchKernelGGL((mean_logit_softmax_kernel<D_>), glog, dim3(256), 0, st, pp); \
+  } while (0)
   if (s->head_dim == 128 && s->block == 128)
     SP_POOL(128, 128);
   else if (s->head_dim == 128 && s->block == 64)
@@ -1318,15 +1413,42 @@ sp_status launch_mean_logit_scores(const sp_shape *s, const void *q, const void 
   else
     SP_POOL(64, 64);
 #undef SP_POOL
-  sp_status rc = hip_check(hipGetLastError(), "block_pool_kernel launch");
+  return hip_check(hipGetLastError(), "block-mean-logit score kernels launch");
+}
+
+// Alg. 3 for the listed heads: estimates (last query-block row of the score map) into a_hat, then the gate
+sp_status launch_determine(const sp_shape *s, const void *q, const void *k, const int32_t *heads, int n,
+                           const int32_t *ref_pos, const int32_t *shared_map, float delta, float tau, float *a_hat,
+                           float *dist, int32_t *head_pattern, char *pattern_ws, hipStream_t st) {
+  const int nqb = s->seq / s->block;
+  sp_status rc = launch_mean_logit_scores(s, q, k, heads, n, nqb - 1, 1, a_hat, pattern_ws, st);
   if (rc) return rc;
-  if (s->head_dim == 128)
-    hipLaunchKernelGGL(mean_logit_softmax_kernel<128>, glog, dim3(256), 0, st, pp.qsum, pp.ksumT, pp.diag, scores,
-                       nqb, c_full, c_diag);
-  else
-    hipLaunchKernelGGL(mean_logit_softmax_kernel<64>, glog, dim3(256), 0, st, pp.qsum, pp.ksumT, pp.diag, scores,
-                       nqb, c_full, c_diag);
-  return hip_check(hipGetLastError(), "mean_logit_softmax_kernel launch");
+  GateParams gp;
+  memset(&gp, 0, sizeof(gp));
+  gp.a_hat = a_hat;
+  gp.dist = dist;
+  gp.head_pattern = head_pattern;
+  gp.nkb = nqb;
+  gp.n_heads = n;
+  gp.n_q_heads = s->n_q_heads;
+  gp.delta = delta;
+  gp.tau = tau;
+  for (int a = 0; a < n; ++a) {
+    gp.head_ids[a] = heads[a];
+    gp.ref_pos[a] = ref_pos[a];
+    gp.shared_map[a] = shared_map[a];
+  }
+  ProfScope prof(KK_SCORE, st);
+  hipLaunchKernelGGL(js_gate_kernel, dim3(n, s->batch), dim3(256), 0, st, gp);
+  return hip_check(hipGetLastError(), "js_gate_kernel launch");
+}
+
+sp_status check_thresholds(float delta, float tau) {
+  if (!(delta >= 0.f) || !(tau >= 0.f) || std::isinf(delta) || std::isinf(tau)) {
+    set_err("delta %g / tau %g must be finite and >= 0", (double)delta, (double)tau);
+    return SP_ERR_INVALID_ARG;
+  }
+  return SP_OK;
 }
 
 // Alg. 2 over each flattened map; `scratch` holds n_maps * gsel_map_bytes(nqb) bytes
@@ -1434,7 +1556,8 @@ sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_
     set_err("n_dense_heads %d outside [0, %d]", n_dense_heads, shape->n_q_heads);
     return SP_ERR_INVALID_ARG;
   }
-  *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads) + pattern_layout(shape, n_dense_heads).total;
+  *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads) +
+           std::max(pattern_layout(shape, n_dense_heads).total, pattern_layout(shape, shape->n_q_heads).total);
   return SP_OK;
 }
 
@@ -1526,10 +1649,11 @@ sp_status sp_build_block_mask(const float *block_scores, int32_t n_maps, int32_t
   return launch_mask(block_scores, n_maps, nqb, nkb, gamma, kb_idx, kb_cnt, bitmask, (hipStream_t)hip_stream);
 }
 
-sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void *k, const void *v,
-                               const int32_t *head_ids, const int32_t *head_map, int32_t n_heads,
-                               const int32_t *kb_idx, const int32_t *kb_cnt, int32_t n_maps, void *o,
-                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+static sp_status sparse_attn_impl(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                  const int32_t *head_ids, const int32_t *head_map, int32_t n_heads,
+                                  const int32_t *kb_idx, const int32_t *kb_cnt, int32_t n_maps,
+                                  const int32_t *head_pattern, void *o, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream) {
   g_err[0] = 0;
   sp_status rc = check_shape(shape);
   if (rc) return rc;
@@ -1537,15 +1661,15 @@ sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void 
       (rc = check_ptr16(o, "o")))
     return rc;
   if ((rc = check_heads(shape, head_ids, n_heads, "head_ids"))) return rc;
-  if (!head_map || !kb_idx || !kb_cnt) {
-    set_err("head_map / kb_idx / kb_cnt must not be NULL");
+  if ((!head_map && !head_pattern) || !kb_idx || !kb_cnt) {
+    set_err("head_map / head_pattern / kb_idx / kb_cnt must not be NULL");
     return SP_ERR_INVALID_ARG;
   }
   if (n_maps <= 0) {
     set_err("n_maps must be positive");
     return SP_ERR_INVALID_ARG;
   }
-  for (int a = 0; a < n_heads; ++a)
+  for (int a = 0; head_map && a < n_heads; ++a)
     if (head_map[a] < 0 || head_map[a] >= n_maps) {
       set_err("head_map[%d] = %d outside [0, %d)", a, head_map[a], n_maps);
       return SP_ERR_INVALID_ARG;
@@ -1560,11 +1684,63 @@ sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void 
   ap.n_maps = n_maps;
   for (int a = 0; a < n_heads; ++a) {
     hl.head[a] = head_ids[a];
-    hl.map[a] = head_map[a];
+    hl.map[a] = head_map ? head_map[a] : 0;
   }
+  ap.head_pattern = head_pattern;
+  ap.n_q_heads = shape->n_q_heads;
   ap.kb_idx = kb_idx;
   ap.kb_cnt = kb_cnt;
   return launch_attn<false>(shape, ap, hl, st);
+}
+
+sp_status sp_block_sparse_attn(const sp_shape *shape, const void *q, const void *k, const void *v,
+                               const int32_t *head_ids, const int32_t *head_map, int32_t n_heads,
+                               const int32_t *kb_idx, const int32_t *kb_cnt, int32_t n_maps, void *o,
+                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+  if (!head_map) {
+    g_err[0] = 0;
+    set_err("head_map must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  return sparse_attn_impl(shape, q, k, v, head_ids, head_map, n_heads, kb_idx, kb_cnt, n_maps, nullptr, o, workspace,
+                          workspace_bytes, hip_stream);
+}
+
+sp_status sp_block_sparse_attn_gated(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                     const int32_t *head_ids, int32_t n_heads, const int32_t *kb_idx,
+                                     const int32_t *kb_cnt, int32_t n_maps, const int32_t *head_pattern, void *o,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+  if (!head_pattern) {
+    g_err[0] = 0;
+    set_err("head_pattern must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  return sparse_attn_impl(shape, q, k, v, head_ids, nullptr, n_heads, kb_idx, kb_cnt, n_maps, head_pattern, o,
+                          workspace, workspace_bytes, hip_stream);
+}
+
+sp_status sp_determine_pattern(const sp_shape *shape, const void *q, const void *k, const int32_t *head_ids,
+                               int32_t n_heads, const int32_t *ref_pos, const int32_t *shared_map, float delta,
+                               float tau, float *a_hat, float *dist, int32_t *head_pattern, void *workspace,
+                               size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k"))) return rc;
+  if ((rc = check_heads(shape, head_ids, n_heads, "head_ids"))) return rc;
+  if (!ref_pos || !shared_map || !a_hat || !dist || !head_pattern) {
+    set_err("ref_pos / shared_map / a_hat / dist / head_pattern must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  for (int a = 0; a < n_heads; ++a)
+    if (ref_pos[a] < -1 || ref_pos[a] >= n_heads) {
+      set_err("ref_pos[%d] = %d outside [-1, %d)", a, ref_pos[a], n_heads);
+      return SP_ERR_INVALID_ARG;
+    }
+  if ((rc = check_thresholds(delta, tau))) return rc;
+  if ((rc = check_ws(workspace, workspace_bytes, pattern_layout(shape, n_heads).gsel))) return rc;
+  return launch_determine(shape, q, k, head_ids, n_heads, ref_pos, shared_map, delta, tau, a_hat, dist, head_pattern,
+                          (char *)workspace, (hipStream_t)hip_stream);
 }
 
 sp_status sp_block_mean_logit_scores(const sp_shape *shape, const void *q, const void *k, const int32_t *head_ids,
@@ -1580,7 +1756,8 @@ sp_status sp_block_mean_logit_scores(const sp_shape *shape, const void *q, const
     return SP_ERR_INVALID_ARG;
   }
   if ((rc = check_ws(workspace, workspace_bytes, pattern_layout(shape, n_heads).gsel))) return rc;
-  return launch_mean_logit_scores(shape, q, k, head_ids, n_heads, block_scores, (char *)workspace,
+  return launch_mean_logit_scores(shape, q, k, head_ids, n_heads, 0, shape->seq / shape->block, block_scores,
+                                  (char *)workspace,
                                   (hipStream_t)hip_stream);
 }
 
@@ -1614,11 +1791,13 @@ sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, 
                             (hipStream_t)hip_stream);
 }
 
-sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const void *k, const void *v,
-                                 const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
-                                 float gamma, int32_t score_mode, int32_t select_mode, void *o, float *block_scores,
-                                 int32_t *kb_idx, int32_t *kb_cnt, void *workspace, size_t workspace_bytes,
-                                 void *hip_stream) {
+// a_hat / dist / head_pattern all NULL: no gate (every clustered head shares its pivot's pattern)
+static sp_status prefill_impl(const sp_shape *shape, const void *q, const void *k, const void *v,
+                              const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                              float gamma, int32_t score_mode, int32_t select_mode, bool gated, float delta, float tau,
+                              void *o, float *block_scores, int32_t *kb_idx, int32_t *kb_cnt, float *a_hat,
+                              float *dist, int32_t *head_pattern, void *workspace, size_t workspace_bytes,
+                              void *hip_stream) {
   g_err[0] = 0;
   sp_status rc = check_shape(shape);
   if (rc) return rc;
@@ -1661,12 +1840,20 @@ sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const voi
     }
     is_pivot[ph] = true;
   }
+  if (gated) {
+    if (!a_hat || !dist || !head_pattern) {
+      set_err("a_hat / dist / head_pattern must not be NULL");
+      return SP_ERR_INVALID_ARG;
+    }
+    if ((rc = check_thresholds(delta, tau))) return rc;
+  }
   const bool mass = score_mode == SP_SCORE_BLOCK_MASS;
-  const bool pattern_ws = !mass || select_mode == SP_SELECT_GLOBAL;
+  const bool pattern_ws = !mass || select_mode == SP_SELECT_GLOBAL || gated;
   const size_t off_lws = pack_bytes(shape);
   const size_t off_pat = off_lws + (mass ? lws_bytes(shape, n_clusters) : 0);
   const PatternLayout PL = pattern_layout(shape, n_clusters);
-  const size_t need = off_pat + (pattern_ws ? PL.total : 0);
+  const PatternLayout PG = pattern_layout(shape, Hq);  // the gate pools every head
+  const size_t need = off_pat + (pattern_ws ? (gated ? PG.total : PL.total) : 0);
   if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   const int nqb = shape->seq / shape->block;
@@ -1685,7 +1872,7 @@ sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const voi
     ap.scores = block_scores;
   }
   if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
-  if (!mass && (rc = launch_mean_logit_scores(shape, q, k, pivot_heads, n_clusters, block_scores, ws + off_pat, st)))
+  if (!mass && (rc = launch_mean_logit_scores(shape, q, k, pivot_heads, n_clusters, 0, nqb, block_scores, ws + off_pat, st)))
     return rc;
   // 2. heads outside every cluster: dense, no scores
   fill_attn(ap, shape, q, workspace, o);
@@ -1695,12 +1882,24 @@ sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const voi
   if (hl.n) {
     if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
   }
+  // 2b. Alg. 3: every head's last-row estimate, the pivot's serving as its cluster's representative;
+  //     heads outside every cluster and pivots keep running dense whatever the gate says
+  if (gated) {
+    int32_t all[SP_MAX_HEADS], ref[SP_MAX_HEADS], smap[SP_MAX_HEADS];
+    for (int hq = 0; hq < Hq; ++hq) {
+      all[hq] = hq;
+      ref[hq] = head_to_cluster[hq] >= 0 ? pivot_heads[head_to_cluster[hq]] : -1;
+      smap[hq] = head_to_cluster[hq];  // -1 for unclustered heads: never shared
+    }
+    if ((rc = launch_determine(shape, q, k, all, Hq, ref, smap, delta, tau, a_hat, dist, head_pattern, ws + off_pat, st)))
+      return rc;
+  }
   // 3. one pattern per (batch, cluster) (Alg. 2: per query-block row, or over the flattened map)
   if (select_mode == SP_SELECT_PER_ROW)
     rc = launch_mask(block_scores, shape->batch * n_clusters, nqb, nqb, gamma, kb_idx, kb_cnt, nullptr, st);
   else
     rc = launch_mask_global(block_scores, shape->batch * n_clusters, nqb, gamma, 1, kb_idx, kb_cnt,
-                            ws + off_pat + PL.gsel, st);
+                            ws + off_pat + (gated ? PG.gsel : PL.gsel), st);
   if (rc) return rc;
   // 4. remaining heads share their cluster's pattern (Alg. 4) and run block-sparse (Sec. 5.1)
   fill_attn(ap, shape, q, workspace, o);
@@ -1715,10 +1914,33 @@ sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const voi
     ap.n_maps = n_clusters;
     ap.kb_idx = kb_idx;
     ap.kb_cnt = kb_cnt;
+    ap.head_pattern = gated ? head_pattern : nullptr;
+    ap.n_q_heads = Hq;
     if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
   }
   return SP_OK;
 }
+
+sp_status sp_prefill_layer_modes(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                 const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                                 float gamma, int32_t score_mode, int32_t select_mode, void *o, float *block_scores,
+                                 int32_t *kb_idx, int32_t *kb_cnt, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream) {
+  return prefill_impl(shape, q, k, v, head_to_cluster, pivot_heads, n_clusters, gamma, score_mode, select_mode, false,
+                      0.f, 0.f, o, block_scores, kb_idx, kb_cnt, nullptr, nullptr, nullptr, workspace, workspace_bytes,
+                      hip_stream);
+}
+
+sp_status sp_prefill_layer_gated(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                 const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
+                                 float gamma, float delta, float tau, int32_t score_mode, int32_t select_mode, void *o,
+                                 float *block_scores, int32_t *kb_idx, int32_t *kb_cnt, float *a_hat, float *dist,
+                                 int32_t *head_pattern, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return prefill_impl(shape, q, k, v, head_to_cluster, pivot_heads, n_clusters, gamma, score_mode, select_mode, true,
+                      delta, tau, o, block_scores, kb_idx, kb_cnt, a_hat, dist, head_pattern, workspace,
+                      workspace_bytes, hip_stream);
+}
+
 
 sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
                            const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,

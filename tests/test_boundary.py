@@ -35,12 +35,17 @@ def test_workspace_bytes_and_shape_validation():
     import paper_2505_19578_amd as sp
     s = _shape(sp)
     pack = 1 * 4 * 1024 * 64 * 2 * 2
-    assert sp.sp_workspace_bytes(s, 0) == pack
-    score_ws = 2 * (2 * 16 * 64 * 4) + 256                       # per-block sums of Q and K + diagonal sums
-    mask_ws = -(-(2 * (2 * 4104 * 8 + 64 + 256)) // 256) * 256   # two histograms + state + per-row counters, per map
-    assert sp.sp_score_workspace_bytes(s, 2) == score_ws
-    assert sp.sp_mask_workspace_bytes(2, 16) == mask_ws
-    assert sp.sp_workspace_bytes(s, 2) == pack + 2 * 16 * 16 * 64 * 4 + score_ws + mask_ws
+    def score_ws(n):    # key sums of every KV head, query sums + diagonal sums of n heads
+        return 4 * 16 * 64 * 4 + n * 16 * 64 * 4 + 256
+
+    def mask_ws(n):     # two histograms + state + per-row counters, per map
+        return -(-(n * (2 * 4104 * 8 + 64 + 256)) // 256) * 256
+
+    assert sp.sp_score_workspace_bytes(s, 2) == score_ws(2)
+    assert sp.sp_mask_workspace_bytes(2, 16) == mask_ws(2)
+    # the attention calls' workspace also covers the gate, which pools all 4 heads
+    assert sp.sp_workspace_bytes(s, 0) == pack + score_ws(4) + mask_ws(4)
+    assert sp.sp_workspace_bytes(s, 2) == pack + 2 * 16 * 16 * 64 * 4 + score_ws(4) + mask_ws(4)
     with pytest.raises(sp.SpError):
         sp.sp_mask_workspace_bytes(0, 16)
     with pytest.raises(sp.SpError):
@@ -122,6 +127,28 @@ def test_calls_reject_bad_arguments_without_launching():
     rc = L.sp_prefill_layer_modes(ctypes.byref(s), fake, fake, fake, h2c, piv, 2, ctypes.c_float(0.9), 1, 1, fake,
                                   fake, fake, fake, fake, 16, None)
     assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    # Alg. 3 gate
+    ref = (ctypes.c_int32 * 4)(0, 0, 2, 9)
+    rc = L.sp_determine_pattern(ctypes.byref(s), fake, fake, ids, 4, ref, h2c, ctypes.c_float(0.3),
+                                ctypes.c_float(0.2), fake, fake, fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"ref_pos" in L.sp_last_error()
+    ref = (ctypes.c_int32 * 4)(0, 0, 2, 2)
+    rc = L.sp_determine_pattern(ctypes.byref(s), fake, fake, ids, 4, ref, h2c, ctypes.c_float(-0.3),
+                                ctypes.c_float(0.2), fake, fake, fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"delta" in L.sp_last_error()
+    rc = L.sp_determine_pattern(ctypes.byref(s), fake, fake, ids, 4, ref, h2c, ctypes.c_float(0.3),
+                                ctypes.c_float(0.2), fake, None, fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    rc = L.sp_determine_pattern(ctypes.byref(s), fake, fake, ids, 4, ref, h2c, ctypes.c_float(0.3),
+                                ctypes.c_float(0.2), fake, fake, fake, fake, 128, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    rc = L.sp_block_sparse_attn_gated(ctypes.byref(s), fake, fake, fake, ids, 4, fake, fake, 2, None, fake, fake,
+                                      1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"head_pattern" in L.sp_last_error()
+    rc = L.sp_prefill_layer_gated(ctypes.byref(s), fake, fake, fake, h2c, piv, 2, ctypes.c_float(0.9),
+                                  ctypes.c_float(0.3), ctypes.c_float(0.2), 0, 0, fake, fake, fake, fake, fake, None,
+                                  fake, fake, 1 << 30, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"dist" in L.sp_last_error()
 
 
 def test_generator_is_deterministic_and_bf16_round_trip():
