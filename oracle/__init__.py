@@ -20,6 +20,9 @@ Stages (one attention head at a time, arrays are float32 ``[N][d]``):
                       Alg. 3 (Determine Sparse Pattern): the last query block's
                       block-averaged attention estimate, its Jensen-Shannon distances to
                       the uniform distribution and to the pivot's representative, the gate
+* ``prefill_layers_dict`` Alg. 1 head by head, layer by layer, with the dynamic pivotal
+                      pattern dictionary (Sec. 5.2): first qualifying head of a cluster runs
+                      dense and installs the pattern, later heads, in this or later layers, share it
 * ``prefill_layer``   Alg. 1 / Alg. 4 for one layer with given pivots: pivots run
                       dense, their score map becomes the cluster's pattern, all
                       other heads of the cluster run masked attention with it.
@@ -314,3 +317,61 @@ def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: floa
         else:
             o[:, h] = masked_rows(q[:, h], k[:, g], v[:, g], block, kb_idx[c], kb_cnt[c], rows, scale)
     return {"o": o, "scores": scores, "kb_idx": kb_idx, "kb_cnt": kb_cnt, "shared": decided, "dist": dist}
+
+
+ROLE_FALLBACK, ROLE_PIVOT = -1, -2
+
+
+def prefill_layers_dict(layers, block: int, gamma: float, delta: float, tau: float, paper_pattern: bool = False,
+                        scale: Optional[float] = None, pattern_dict: Optional[dict] = None):
+    """Alg. 1 applied head by head (ascending head index), layer by layer, with the pivotal pattern
+    dictionary of Sec. 5.2 carried across layers.
+
+    `layers` is a list of dicts with q [N][Hq][d], k, v [N][Hkv][d] float32 and head_to_cluster [Hq]
+    (cluster ids shared by all layers, -1 = no cluster).  For each head of a cluster c:
+      Alg. 3 decides with the dictionary's representative a~ of c (no entry: only the sparsity test);
+      shared_pivot and an entry exists  -> masked attention with the entry's lists (Alg. 4), role c;
+      shared_pivot and no entry         -> dense attention (all-ones pattern), then Alg. 2 builds the
+                                           lists and the entry (a~ = this head's estimate), role -2;
+      otherwise                          -> the fallback pattern (dense here), role -1, no update.
+    Heads without a cluster run dense (role -1).  Every row of every map is needed.
+
+    Returns (results, pattern_dict): results[l] = {"o", "role" [Hq], "dist" [Hq][2]};
+    pattern_dict[c] = {"a_tilde", "kb_idx", "kb_cnt", "scores", "layer", "head"}."""
+    D = {} if pattern_dict is None else pattern_dict
+    results = []
+    for l, Lr in enumerate(layers):
+        q = np.asarray(Lr["q"], dtype=np.float32)
+        k = np.asarray(Lr["k"], dtype=np.float32)
+        v = np.asarray(Lr["v"], dtype=np.float32)
+        h2c = [int(x) for x in Lr["head_to_cluster"]]
+        N, Hq, d = q.shape
+        G = Hq // k.shape[1]
+        o = np.zeros((N, Hq, d), dtype=np.float32)
+        role = np.full(Hq, ROLE_FALLBACK, dtype=np.int32)
+        dist = np.zeros((Hq, 2), dtype=np.float64)
+        for h in range(Hq):
+            c, g = h2c[h], h // G
+            qh, kh, vh = q[:, h], k[:, g], v[:, g]
+            shared = False
+            if c >= 0:
+                a_hat = last_row_estimate(qh, kh, block, scale)
+                entry = D.get(c)
+                shared, dist[h, 0], dist[h, 1] = determine_pattern(
+                    a_hat, None if entry is None else entry["a_tilde"], delta, tau)
+            if shared and entry is not None:
+                o[:, h] = masked_rows(qh, kh, vh, block, entry["kb_idx"], entry["kb_cnt"], None, scale)
+                role[h] = c
+            elif shared:
+                o[:, h], sc, _ = dense_rows(qh, kh, vh, block, None, scale, want_scores=not paper_pattern)
+                if paper_pattern:
+                    sc = softmax_rows(mean_logit_rows(qh, kh, block, None, scale))
+                    idx, cnt, _ = build_mask_global(sc, gamma, forced=True)
+                else:
+                    idx, cnt, _ = build_mask_rows(sc, gamma)
+                D[c] = {"a_tilde": a_hat, "kb_idx": idx, "kb_cnt": cnt, "scores": sc, "layer": l, "head": h}
+                role[h] = ROLE_PIVOT
+            else:
+                o[:, h], _, _ = dense_rows(qh, kh, vh, block, None, scale, want_scores=False)
+        results.append({"o": o, "role": role, "dist": dist})
+    return results, D

@@ -123,7 +123,7 @@ def _topic_sequence(cfg: LayerConfig, rng: np.random.Generator, N: int) -> np.nd
 
 
 def make_layer(cfg: LayerConfig, layer: int = 0, seq: Optional[int] = None,
-               heads: Optional[List[int]] = None) -> dict:
+               heads: Optional[List[int]] = None, structure_layer: Optional[int] = None) -> dict:
     """Generate one layer's inputs.
 
     Returns a dict with
@@ -133,6 +133,9 @@ def make_layer(cfg: LayerConfig, layer: int = 0, seq: Optional[int] = None,
       head_to_cluster int32 [Hq], pivot_heads int32 [C], cfg (with seq applied), seed
 
     `seq` overrides the sequence length (same recipe, shorter prefix statistics).
+    `structure_layer`, if given, takes the prompt-dependent structure (cluster membership, topic
+    sequences, heavy vertical positions) from that layer's streams while the projections and the
+    noise stay this layer's own: layers of one prompt, whose clusters span the layers.
     """
     if seq is not None and seq != cfg.seq:
         cfg = replace(cfg, seq=int(seq))
@@ -140,12 +143,13 @@ def make_layer(cfg: LayerConfig, layer: int = 0, seq: Optional[int] = None,
     if N % cfg.block:
         raise ValueError("seq must be a multiple of block")
     seed = 1000 * cfg.index + layer
+    sseed = seed if structure_layer is None else 1000 * cfg.index + int(structure_layer)
     G = cfg.group
-    h2c, piv = _clusters(cfg, seed)
+    h2c, piv = _clusters(cfg, sseed)
     C, r = cfg.n_clusters, cfg.rank
 
     g = float(np.sqrt(cfg.topic_gain * np.sqrt(d)))
-    topics = [_topic_sequence(cfg, _rng(seed, 10, c), N) for c in range(C)]
+    topics = [_topic_sequence(cfg, _rng(sseed, 10, c), N) for c in range(C)]
     A = [(_rng(seed, 11, c).standard_normal((r, d)) / np.sqrt(d)).astype(np.float32) for c in range(C)]
     A2 = [(_rng(seed, 12, c).standard_normal((r, d)) / np.sqrt(d)).astype(np.float32) for c in range(C)]
     e_s = _rng(seed, 13).standard_normal(d)
@@ -154,7 +158,7 @@ def make_layer(cfg: LayerConfig, layer: int = 0, seq: Optional[int] = None,
     b = np.zeros(N, dtype=np.float32)
     b[0] = cfg.sink_boost
     if cfg.n_heavy > 0 and N > 1:
-        heavy = _rng(seed, 14).choice(np.arange(1, N), size=min(cfg.n_heavy, N - 1), replace=False)
+        heavy = _rng(sseed, 14).choice(np.arange(1, N), size=min(cfg.n_heavy, N - 1), replace=False)
         b[heavy] = cfg.heavy_boost
     else:
         heavy = np.zeros(0, dtype=np.int64)

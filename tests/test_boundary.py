@@ -161,6 +161,13 @@ def test_generator_is_deterministic_and_bf16_round_trip():
     assert list(a["head_to_cluster"]) == [0, 0, 1, 1] and list(a["pivot_heads"]) == [0, 2]
     c = make_layer(CONFIGS["tiny"], layer=1, seq=256)
     assert not np.array_equal(a["q"], c["q"])
+    # layers of one prompt: structure (clusters, heavy positions) from layer 0, projections / noise of their own
+    p0 = make_layer(CONFIGS["qwen7b_128k"], layer=0, seq=512)
+    p1 = make_layer(CONFIGS["qwen7b_128k"], layer=1, seq=512, structure_layer=0)
+    own = make_layer(CONFIGS["qwen7b_128k"], layer=1, seq=512)
+    assert np.array_equal(p0["head_to_cluster"], p1["head_to_cluster"]) and np.array_equal(p0["heavy"], p1["heavy"])
+    assert not np.array_equal(p0["head_to_cluster"], own["head_to_cluster"])
+    assert not np.array_equal(p0["q"], p1["q"]) and p1["seed"] == own["seed"]
     x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.0e38], dtype=np.float32)
     bits = f32_to_bf16_bits(x)
     # 1 + 2^-8 is a tie -> even (1.0); 1 + 3*2^-8 is a tie -> even (1 + 2^-6)
