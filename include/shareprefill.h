@@ -259,6 +259,49 @@ sp_status sp_prefill_layer_gated(const sp_shape *shape, const void *q, const voi
                                  float *block_scores, int32_t *kb_idx, int32_t *kb_cnt, float *a_hat, float *dist,
                                  int32_t *head_pattern, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The dynamic pivotal pattern dictionary (Sec. 5.2, "Dynamic Pattern Construction and Sharing
+ * during Inference"): for every cluster of the offline head dictionary, the pattern its first
+ * qualifying head produced and that head's representative a~.  All arrays are caller-owned
+ * device memory that lives across the layers of one prefill; `valid` must be zeroed before
+ * the first layer.  Cluster ids are global: the same id in two layers means the same cluster.
+ */
+typedef struct {
+  int32_t n_clusters;
+  int32_t *valid;   /* device int32 [batch][n_clusters]            1 once the cluster has an entry */
+  float *a_tilde;   /* device fp32  [batch][n_clusters][nkb]       representative (Alg. 2, "last row") */
+  int32_t *kb_idx;  /* device int32 [batch][n_clusters][nqb][nkb]  key-block lists, ascending, tail -1 */
+  int32_t *kb_cnt;  /* device int32 [batch][n_clusters][nqb] */
+} sp_pattern_dict;
+
+/*
+ * One layer of Alg. 1 with the dictionary carried across layers (Alg. 3 decides, Alg. 4 shares,
+ * Alg. 2 constructs).  Heads are taken in ascending index order.  For a head of cluster c:
+ *   - c has an entry: the head shares the entry's pattern iff d_sparse < delta and
+ *     d_sim(a_hat, entry's a~) < tau (role c), else it falls back (role -1);
+ *   - c has no entry: the first head of c in this layer with d_sparse < delta (and 0 < tau: with
+ *     no representative d_sim counts as 0) is elected pivot (role -2): it runs dense attention,
+ *     its score map becomes the entry's pattern (Alg. 2 per score_mode / select_mode as in
+ *     sp_prefill_layer_modes) and its estimate the entry's a~; the heads after it are tested
+ *     against that estimate; heads before it, and all heads if none qualifies, fall back.
+ *   Heads with cluster -1 and fallback heads run dense attention (the stand-in for Alg. 5) and
+ *   never touch the dictionary.  Everything is decided on the device: one stream, no host
+ *   synchronisation; the roles can be read back afterwards.
+ *   head_to_cluster host [n_q_heads] global cluster id in [0, dict->n_clusters) or -1
+ *   block_scores    device fp32 [batch][n_slots][nqb][nkb], n_slots = number of distinct clusters
+ *                   in head_to_cluster (ascending cluster id); slot s is written only if its
+ *                   cluster elected a pivot in this call
+ *   role            device int32 [batch][n_q_heads]      (output)
+ *   a_hat, dist     device fp32 [batch][n_q_heads][nkb] / [batch][n_q_heads][2]   (outputs, Alg. 3; heads
+ *                   without a cluster get their estimate and d_sparse too, with d_sim = 0)
+ *   workspace       sp_workspace_bytes(shape, n_slots)
+ */
+sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                const int32_t *head_to_cluster, float gamma, float delta, float tau,
+                                int32_t score_mode, int32_t select_mode, const sp_pattern_dict *dict, void *o,
+                                float *block_scores, int32_t *role, float *a_hat, float *dist, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "sp_block_sparse_attn", "sp_prefill_layer",
     "sp_score_workspace_bytes", "sp_mask_workspace_bytes", "sp_block_mean_logit_scores",
     "sp_build_block_mask_global", "sp_prefill_layer_modes",
-    "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated",
+    "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated", "sp_prefill_layer_dict",
 ]
 
 SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT = 0, 1
@@ -33,6 +33,11 @@ class SpShape(ctypes.Structure):
         ("o_stride_b", ctypes.c_int64), ("o_stride_t", ctypes.c_int64), ("o_stride_h", ctypes.c_int64),
         ("softmax_scale", ctypes.c_float),
     ]
+
+
+class SpPatternDict(ctypes.Structure):
+    _fields_ = [("n_clusters", ctypes.c_int32), ("valid", ctypes.c_void_p), ("a_tilde", ctypes.c_void_p),
+                ("kb_idx", ctypes.c_void_p), ("kb_cnt", ctypes.c_void_p)]
 
 
 class SpError(RuntimeError):
@@ -100,6 +105,10 @@ def lib() -> ctypes.CDLL:
         L.sp_prefill_layer_gated.argtypes = [sp, vp, vp, vp, ip, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
                                              ctypes.c_float, ctypes.c_int32, ctypes.c_int32, vp, fp, vp, vp, fp, fp,
                                              vp, vp, ctypes.c_size_t, vp]
+        L.sp_prefill_layer_dict.restype = ctypes.c_int
+        L.sp_prefill_layer_dict.argtypes = [sp, vp, vp, vp, ip, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                            ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(SpPatternDict), vp, fp,
+                                            vp, fp, fp, vp, ctypes.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -249,3 +258,22 @@ def sp_prefill_layer_gated(shape: SpShape, q, k, v, head_to_cluster, pivot_heads
         len(pivot_heads), ctypes.c_float(gamma), ctypes.c_float(delta), ctypes.c_float(tau), int(score_mode),
         int(select_mode), _ptr(o), _ptr(block_scores), _ptr(kb_idx), _ptr(kb_cnt), _ptr(a_hat), _ptr(dist),
         _ptr(head_pattern), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def pattern_dict_of(valid, a_tilde, kb_idx, kb_cnt) -> SpPatternDict:
+    """sp_pattern_dict over caller-owned device tensors valid [b][C], a_tilde [b][C][nkb],
+    kb_idx [b][C][nqb][nkb], kb_cnt [b][C][nqb] (the returned struct only points at them: keep them alive)."""
+    d = SpPatternDict()
+    d.n_clusters = valid.shape[1]
+    d.valid, d.a_tilde, d.kb_idx, d.kb_cnt = valid.data_ptr(), a_tilde.data_ptr(), kb_idx.data_ptr(), kb_cnt.data_ptr()
+    return d
+
+
+def sp_prefill_layer_dict(shape: SpShape, q, k, v, head_to_cluster, gamma: float, delta: float, tau: float,
+                          score_mode: int, select_mode: int, pattern_dict: SpPatternDict, o, block_scores, role,
+                          a_hat, dist, workspace):
+    _check(lib().sp_prefill_layer_dict(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_to_cluster), ctypes.c_float(gamma),
+        ctypes.c_float(delta), ctypes.c_float(tau), int(score_mode), int(select_mode), ctypes.byref(pattern_dict),
+        _ptr(o), _ptr(block_scores), _ptr(role), _ptr(a_hat), _ptr(dist), _ptr(workspace), _nbytes(workspace),
+        _stream()))

@@ -161,8 +161,11 @@ struct AttnParams {
   const int32_t *kb_cnt;  // sparse: [b][n_maps][nqb]
   // sparse, optional: per (batch entry, query head) pattern chosen on the device (Alg. 3's gate):
   // a list index in [0, n_maps), or < 0 = no shared pattern, the head walks every key block 0..i
-  const int32_t *head_pattern;  // [b][n_q_heads]
+  const int32_t *head_pattern;  // [b][n_q_heads]; <= -2 = nothing to do for this head in this launch
   int n_q_heads;
+  // optional: the query head of listed position n, chosen on the device (pivot election): [b][n_heads],
+  // negative = this position is empty
+  const int32_t *head_dev;
   int32_t head_ids[SP_MAX_SLOTS];  // query head of each slot, -1 = padding slot
   int32_t head_map[SP_MAX_SLOTS];  // sparse: which list the slot's head uses
   int32_t head_pos[SP_MAX_SLOTS];  // position of the head in the caller's list (scores / lws index)
@@ -253,10 +256,14 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   rest /= p.ncol;
   const int i = p.nqb - 1 - (rest % p.nqb);
   const int b = rest / p.nqb;
-  const int head = p.head_ids[slot];
+  int head = p.head_ids[slot];
   if (head < 0) return;  // padding slot
   const int nkb = p.nqb;
   const int hpos = p.head_pos[slot];
+  if (p.head_dev) {
+    head = __builtin_amdgcn_readfirstlane(p.head_dev[(int64_t)b * p.n_heads + hpos]);
+    if (head < 0 || head >= p.n_q_heads) return;
+  }
   const int kvh = head / p.group;
 
   const int tq = 32 * w + c32;  // this lane's query inside the block
@@ -284,6 +291,7 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
     if (p.head_pattern) {
       map = __builtin_amdgcn_readfirstlane(p.head_pattern[(int64_t)b * p.n_q_heads + head]);
       map = map >= p.n_maps ? p.n_maps - 1 : map;
+      if (map <= -2) return;
     }
     if (map < 0) {
       nblk = i + 1;  // list stays null: dense walk
@@ -657,11 +665,19 @@ __device__ __forceinline__ uint32_t quantise24(float s) {
 template <int EPL>
 __global__ __launch_bounds__(256) void mask_kernel(const float *__restrict__ scores, int n_rows_total, int nqb,
                                                    int nkb, uint32_t gq, int32_t *__restrict__ kb_idx,
-                                                   int32_t *__restrict__ kb_cnt, uint64_t *__restrict__ bitmask) {
+                                                   int32_t *__restrict__ kb_cnt, uint64_t *__restrict__ bitmask,
+                                                   const int32_t *__restrict__ route) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= n_rows_total) return;
   const int i = row % nqb;
+  // route (optional, [n_maps]): the map whose lists this map's rows become, negative = leave this map out
+  int64_t orow = row;
+  if (route) {
+    const int dst = route[row / nqb];
+    if (dst < 0) return;
+    orow = (int64_t)dst * nqb + i;
+  }
   const float *src = scores + (int64_t)row * nkb;
   const int nchunk = (i >> 6) + 1;  // 64-wide chunks that hold valid key blocks
   uint32_t u[EPL > 0 ? EPL : 1];
@@ -705,7 +721,7 @@ __global__ __launch_bounds__(256) void mask_kernel(const float *__restrict__ sco
     const uint64_t above = sum_ge(vstar + 1u);
     need = (T - above + vstar - 1) / vstar;  // ties taken, lowest key block first
   }
-  int32_t *out = kb_idx + (int64_t)row * nkb;
+  int32_t *out = kb_idx + orow * nkb;
   const int nwords = (nkb + 63) >> 6;
   const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   uint32_t ties_before = 0, n_out = 0;
@@ -729,10 +745,10 @@ __global__ __launch_bounds__(256) void mask_kernel(const float *__restrict__ sco
     const uint64_t smask = __ballot(sel);
     if (sel) out[n_out + __popcll(smask & lt)] = j;
     n_out += __popcll(smask);
-    if (bitmask && lane == 0) bitmask[(int64_t)row * nwords + e] = smask;
+    if (bitmask && lane == 0) bitmask[orow * nwords + e] = smask;
   }
   for (int pos = n_out + lane; pos < nkb; pos += 64) out[pos] = -1;
-  if (lane == 0) kb_cnt[row] = (int32_t)n_out;
+  if (lane == 0) kb_cnt[orow] = (int32_t)n_out;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -752,8 +768,12 @@ struct PoolParams {
   float *diag;       // [b][n][n_rows]      sum over the diagonal block's causal entries of q_t . k_s
   float *out;        // [b][n][n_rows][nqb] row softmax of the block-mean logits
   float c_full, c_diag;
+  const int32_t *head_dev;  // optional [b][n_heads]: head of listed position n chosen on the device, < 0 = empty
   int32_t head_ids[SP_MAX_HEADS];
 };
+__device__ __forceinline__ int pool_head(const PoolParams &p, int b, int n) {
+  return p.head_dev ? p.head_dev[(int64_t)b * p.n_heads + n] : p.head_ids[n];
+}
 
 // The average of q_t . k_s over a full block is (sum_t q_t) . (sum_s k_s) / B^2, so the block-mean
 // logits need only per-block sums of Q and K.  One thread per head dimension, one block per workgroup.
@@ -773,7 +793,8 @@ template <int D, int B>
 __global__ __launch_bounds__(D) void query_pool_kernel(PoolParams p) {
   const int r = blockIdx.x, n = blockIdx.y, b = blockIdx.z, e = threadIdx.x;
   const int i = p.row0 + r;
-  const int head = p.head_ids[n];
+  const int head = pool_head(p, b, n);
+  if (head < 0) return;
   const uint16_t *qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * B * p.q_st + (int64_t)head * p.q_sh + e;
   const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)i * B * p.k_st + (int64_t)(head / p.group) * p.k_sh + e;
   float run = 0.f, qs = 0.f, acc = 0.f;
@@ -817,12 +838,14 @@ __global__ __launch_bounds__(256) void mean_logit_softmax_kernel(PoolParams p) {
   const int64_t hb = blockIdx.y;
   const int b = (int)(hb / p.n_heads), n = (int)(hb % p.n_heads);
   const int nqb = p.nqb;
+  const int head = pool_head(p, b, n);
+  if (head < 0) return;
   for (int x = tid; x < R * D; x += 256) {
     const int r = x / D, e = x % D;
     qs[r][e] = (r0 + r < p.n_rows) ? p.qsum[((hb * p.n_rows) + r0 + r) * D + e] : 0.f;
   }
   __syncthreads();
-  const float *kT = p.ksumT + ((int64_t)b * p.n_kv_heads + p.head_ids[n] / p.group) * D * nqb;
+  const float *kT = p.ksumT + ((int64_t)b * p.n_kv_heads + head / p.group) * D * nqb;
   const int rmax = min(r0 + R - 1, p.n_rows - 1);
   const int imax = p.row0 + rmax;
   for (int j = tid; j <= imax; j += 256) {
@@ -867,48 +890,118 @@ struct GateParams {
   int32_t shared_map[SP_MAX_HEADS];  // value written when the pattern is shared
 };
 
-// sqrt(JSD) of the head's estimate against the uniform distribution and against its representative,
-// natural logarithm, accumulated in fp64 (every per-entry contribution is non-negative); one
-// workgroup per (head, batch entry).
-__global__ __launch_bounds__(256) void js_gate_kernel(GateParams p) {
-  __shared__ double red[2][4];
-  const int n = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+// x ln(x/m) + y ln(y/m), m = (x+y)/2: one entry's contribution to 2*JSD, never negative
+__device__ __forceinline__ double js_term(double x, double y) {
+  const double m = 0.5 * (x + y);
+  double t = 0.0;
+  if (x > 0.0) t += x * log(x / m);
+  if (y > 0.0) t += y * log(y / m);
+  return t;
+}
+// sqrt(JSD(a || ref)) over n entries, natural logarithm, fp64; ref == nullptr: the uniform distribution.
+// Called by a whole wavefront; every lane returns the result.
+__device__ __forceinline__ double js_distance_wave(const float *a, const float *ref, int n, int lane) {
+  const double u = 1.0 / (double)n;
+  double sum = 0.0;
+  for (int j = lane; j < n; j += 64) sum += js_term((double)a[j], ref ? (double)ref[j] : u);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+  const double jsd = 0.5 * sum;
+  return sqrt(jsd > 0.0 ? jsd : 0.0);
+}
+
+// Alg. 3's gate for the listed heads: one wavefront per (head, batch entry).
+__global__ __launch_bounds__(64) void js_gate_kernel(GateParams p) {
+  const int n = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
   const float *a = p.a_hat + ((int64_t)b * p.n_heads + n) * p.nkb;
   const int rp = p.ref_pos[n];
-  const float *ref = (rp >= 0) ? p.a_hat + ((int64_t)b * p.n_heads + rp) * p.nkb : nullptr;
-  const double u = 1.0 / (double)p.nkb;
-  auto term = [](double x, double y) -> double {  // x ln(x/m) + y ln(y/m), m = (x+y)/2
-    const double m = 0.5 * (x + y);
-    double t = 0.0;
-    if (x > 0.0) t += x * log(x / m);
-    if (y > 0.0) t += y * log(y / m);
-    return t;
-  };
-  double su = 0.0, sr = 0.0;
-  for (int j = tid; j < p.nkb; j += 256) {
-    const double x = (double)a[j];
-    su += term(x, u);
-    if (ref) sr += term(x, (double)ref[j]);
-  }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    su += __shfl_xor(su, off, 64);
-    sr += __shfl_xor(sr, off, 64);
-  }
+  const double d_sparse = js_distance_wave(a, nullptr, p.nkb, lane);
+  const double d_sim = (rp >= 0) ? js_distance_wave(a, p.a_hat + ((int64_t)b * p.n_heads + rp) * p.nkb, p.nkb, lane) : 0.0;
   if (lane == 0) {
-    red[0][w] = su;
-    red[1][w] = sr;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    const double ju = 0.5 * (red[0][0] + red[0][1] + red[0][2] + red[0][3]);
-    const double jr = 0.5 * (red[1][0] + red[1][1] + red[1][2] + red[1][3]);
-    const double d_sparse = sqrt(ju > 0.0 ? ju : 0.0), d_sim = sqrt(jr > 0.0 ? jr : 0.0);
     const int64_t hb = (int64_t)b * p.n_heads + n;
     p.dist[hb * 2] = (float)d_sparse;
     p.dist[hb * 2 + 1] = (float)d_sim;
     const bool shared = d_sparse < (double)p.delta && d_sim < (double)p.tau;
     p.head_pattern[(int64_t)b * p.n_q_heads + p.head_ids[n]] = shared ? p.shared_map[n] : -1;
+  }
+}
+
+// ---- dynamic pivotal pattern dictionary (Sec. 5.2; Alg. 1 with Alg. 3 and Alg. 4) ----------------
+// Roles written per (batch entry, head): c >= 0 shares cluster c's dictionary pattern, -1 falls back
+// (dense, no update), -2 is elected pivot of its cluster in this layer (dense + pattern construction).
+struct ElectParams {
+  const float *a_hat;   // [b][Hq][nkb] last-row estimates of every head
+  float *dist;          // [b][Hq][2]
+  int32_t *role;        // [b][Hq]
+  int32_t *pivot_head;  // [b][n_slots] head elected for the slot's cluster in this layer, or -1
+  int32_t *route;       // [b][n_slots] dictionary map (b * n_clusters + c) the slot's lists go to, or -1
+  int32_t *valid;       // dictionary [b][n_clusters]
+  float *a_tilde;       // dictionary [b][n_clusters][nkb]
+  int nkb, n_q_heads, n_slots, n_clusters;
+  float delta, tau;
+  int32_t head_cluster[SP_MAX_HEADS];  // global cluster id or -1
+  int32_t head_slot[SP_MAX_HEADS];     // slot of the head's cluster, or -1
+  int32_t slot_cluster[SP_MAX_HEADS];
+};
+
+// One workgroup per batch entry.  Heads are taken in ascending order as in Alg. 1: a cluster without a
+// dictionary entry elects its first head that passes the sparsity test (there is no representative to
+// compare with yet); every other head is tested against the entry's representative, or against the
+// estimate of the pivot elected a moment ago.
+__global__ __launch_bounds__(1024) void elect_kernel(ElectParams p) {
+  __shared__ double ds[SP_MAX_HEADS];
+  __shared__ int piv[SP_MAX_HEADS];
+  __shared__ int had[SP_MAX_HEADS];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const float *ah = p.a_hat + (int64_t)b * p.n_q_heads * p.nkb;
+  for (int h = w; h < p.n_q_heads; h += 16) {
+    const double d = js_distance_wave(ah + (int64_t)h * p.nkb, nullptr, p.nkb, lane);
+    if (lane == 0) ds[h] = d;
+  }
+  __syncthreads();
+  if (tid < p.n_slots) {
+    const int c = p.slot_cluster[tid];
+    const int v = p.valid[(int64_t)b * p.n_clusters + c];
+    int first = -1;
+    if (!v && 0.0 < (double)p.tau)
+      for (int h = p.n_q_heads - 1; h >= 0; --h)
+        if (p.head_cluster[h] == c && ds[h] < (double)p.delta) first = h;
+    piv[tid] = first;
+    had[tid] = v;
+    p.pivot_head[(int64_t)b * p.n_slots + tid] = first;
+    p.route[(int64_t)b * p.n_slots + tid] = first >= 0 ? b * p.n_clusters + c : -1;
+  }
+  __syncthreads();
+  for (int h = w; h < p.n_q_heads; h += 16) {
+    const int c = p.head_cluster[h], s = p.head_slot[h];
+    int role = -1;
+    double d_sim = 0.0;
+    if (c >= 0) {
+      if (piv[s] == h) {
+        role = -2;
+      } else {
+        const float *ref = had[s] ? p.a_tilde + ((int64_t)b * p.n_clusters + c) * p.nkb
+                                  : (piv[s] >= 0 ? ah + (int64_t)piv[s] * p.nkb : nullptr);
+        if (ref) {
+          d_sim = js_distance_wave(ah + (int64_t)h * p.nkb, ref, p.nkb, lane);
+          if (ds[h] < (double)p.delta && d_sim < (double)p.tau) role = c;
+        }
+      }
+    }
+    if (lane == 0) {
+      p.role[(int64_t)b * p.n_q_heads + h] = role;
+      p.dist[((int64_t)b * p.n_q_heads + h) * 2] = (float)ds[h];
+      p.dist[((int64_t)b * p.n_q_heads + h) * 2 + 1] = (float)d_sim;
+    }
+  }
+  __syncthreads();  // every read of the old representatives is done
+  for (int s = 0; s < p.n_slots; ++s) {
+    if (piv[s] < 0) continue;
+    const int c = p.slot_cluster[s];
+    float *dst = p.a_tilde + ((int64_t)b * p.n_clusters + c) * p.nkb;
+    const float *src = ah + (int64_t)piv[s] * p.nkb;
+    for (int j = tid; j < p.nkb; j += 1024) dst[j] = src[j];
+    if (tid == 0) p.valid[(int64_t)b * p.n_clusters + c] = 1;
   }
 }
 
@@ -1097,16 +1190,22 @@ __global__ __launch_bounds__(1024) void gsel_row_scan_kernel(int nqb, char *scra
 // one wavefront per row: ascending list of the kept key blocks (+ sink and diagonal when forced)
 __global__ __launch_bounds__(256) void gsel_emit_kernel(const float *__restrict__ scores, int nqb, char *scratch,
                                                         int forced, int32_t *__restrict__ kb_idx,
-                                                        int32_t *__restrict__ kb_cnt) {
+                                                        int32_t *__restrict__ kb_cnt,
+                                                        const int32_t *__restrict__ route) {
   const int lane = threadIdx.x & 63;
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
   if (i >= nqb) return;
+  int omap = map;
+  if (route) {
+    omap = route[map];
+    if (omap < 0) return;
+  }
   GselView v = gsel_view(scratch, map, nqb);
   const uint32_t vstar = v.state->vstar;
   const uint64_t need = v.state->need;
   const uint64_t before = v.row_before[i];
   const float *src = scores + ((int64_t)map * nqb + i) * nqb;
-  int32_t *out = kb_idx + ((int64_t)map * nqb + i) * nqb;
+  int32_t *out = kb_idx + ((int64_t)omap * nqb + i) * nqb;
   const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   uint32_t ties_seen = 0, n_out = 0;
   for (int j0 = 0; j0 <= i; j0 += 64) {
@@ -1123,7 +1222,7 @@ __global__ __launch_bounds__(256) void gsel_emit_kernel(const float *__restrict_
     n_out += __popcll(smask);
   }
   for (int pos = n_out + lane; pos < nqb; pos += 64) out[pos] = -1;
-  if (lane == 0) kb_cnt[(int64_t)map * nqb + i] = (int32_t)n_out;
+  if (lane == 0) kb_cnt[(int64_t)omap * nqb + i] = (int32_t)n_out;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1347,24 +1446,28 @@ sp_status launch_attn(const sp_shape *s, AttnParams ap, const HeadList &hl, hipS
 }
 
 sp_status launch_mask(const float *scores, int n_maps, int nqb, int nkb, float gamma, int32_t *kb_idx,
-                      int32_t *kb_cnt, uint64_t *bitmask, hipStream_t st) {
+                      int32_t *kb_cnt, uint64_t *bitmask, hipStream_t st, const int32_t *route = nullptr) {
   const uint32_t gq = (uint32_t)rintf(gamma * 16777216.f);
   const int64_t rows = (int64_t)n_maps * nqb;
   dim3 grid((unsigned)((rows + 3) / 4));
   ProfScope prof(KK_MASK, st);
   if (nkb <= 256)
-    hipLaunchKernelGGL(mask_kernel<4>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask);
+    hipLaunchKernelGGL(mask_kernel<4>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask,
+                       route);
   else if (nkb <= 1024)
-    hipLaunchKernelGGL(mask_kernel<16>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask);
+    hipLaunchKernelGGL(mask_kernel<16>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask,
+                       route);
   else
-    hipLaunchKernelGGL(mask_kernel<0>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask);
+    hipLaunchKernelGGL(mask_kernel<0>, grid, dim3(256), 0, st, scores, (int)rows, nqb, nkb, gq, kb_idx, kb_cnt, bitmask,
+                       route);
   return hip_check(hipGetLastError(), "mask_kernel launch");
 }
 
 // row softmax of the block-mean logits of the listed heads, query-block rows row0 .. row0+n_rows-1,
 // into out[b][n][n_rows][nkb]
 sp_status launch_mean_logit_scores(const sp_shape *s, const void *q, const void *k, const int32_t *heads, int n,
-                                   int row0, int n_rows, float *out, char *pattern_ws, hipStream_t st) {
+                                   int row0, int n_rows, float *out, char *pattern_ws, hipStream_t st,
+                                   const int32_t *head_dev = nullptr) {
   if ((int64_t)s->batch * n > 65535) {
     set_err("batch * heads = %lld exceeds 65535", (long long)s->batch * n);
     return SP_ERR_UNSUPPORTED;
@@ -1391,7 +1494,8 @@ sp_status launch_mean_logit_scores(const sp_shape *s, const void *q, const void 
   pp.qsum = (float *)(pattern_ws + L.qsum);
   pp.diag = (float *)(pattern_ws + L.diag);
   pp.out = out;
-  for (int a = 0; a < n; ++a) pp.head_ids[a] = heads[a];
+  pp.head_dev = head_dev;
+  for (int a = 0; a < n; ++a) pp.head_ids[a] = heads ? heads[a] : 0;
   const float scale = (s->softmax_scale > 0.f) ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
   const float B = (float)s->block;
   pp.c_full = scale / (B * B);
@@ -1439,7 +1543,7 @@ sp_status launch_determine(const sp_shape *s, const void *q, const void *k, cons
     gp.shared_map[a] = shared_map[a];
   }
   ProfScope prof(KK_SCORE, st);
-  hipLaunchKernelGGL(js_gate_kernel, dim3(n, s->batch), dim3(256), 0, st, gp);
+  hipLaunchKernelGGL(js_gate_kernel, dim3(n, s->batch), dim3(64), 0, st, gp);
   return hip_check(hipGetLastError(), "js_gate_kernel launch");
 }
 
@@ -1453,7 +1557,7 @@ sp_status check_thresholds(float delta, float tau) {
 
 // Alg. 2 over each flattened map; `scratch` holds n_maps * gsel_map_bytes(nqb) bytes
 sp_status launch_mask_global(const float *scores, int n_maps, int nqb, float gamma, int forced, int32_t *kb_idx,
-                             int32_t *kb_cnt, char *scratch, hipStream_t st) {
+                             int32_t *kb_cnt, char *scratch, hipStream_t st, const int32_t *route = nullptr) {
   if (n_maps > 65535) {
     set_err("%d maps exceed 65535", n_maps);
     return SP_ERR_UNSUPPORTED;
@@ -1469,7 +1573,7 @@ sp_status launch_mask_global(const float *scores, int n_maps, int nqb, float gam
   hipLaunchKernelGGL(gsel_scan_kernel<2>, dim3(n_maps), dim3(1024), 0, st, scratch, nqb, gq);
   hipLaunchKernelGGL(gsel_row_ties_kernel, grows, dim3(256), 0, st, scores, nqb, scratch);
   hipLaunchKernelGGL(gsel_row_scan_kernel, dim3(n_maps), dim3(1024), 0, st, nqb, scratch);
-  hipLaunchKernelGGL(gsel_emit_kernel, grows, dim3(256), 0, st, scores, nqb, scratch, forced, kb_idx, kb_cnt);
+  hipLaunchKernelGGL(gsel_emit_kernel, grows, dim3(256), 0, st, scores, nqb, scratch, forced, kb_idx, kb_cnt, route);
   return hip_check(hipGetLastError(), "global selection kernels launch");
 }
 
@@ -1557,7 +1661,8 @@ sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_
     return SP_ERR_INVALID_ARG;
   }
   *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads) +
-           std::max(pattern_layout(shape, n_dense_heads).total, pattern_layout(shape, shape->n_q_heads).total);
+           std::max(pattern_layout(shape, n_dense_heads).total, pattern_layout(shape, shape->n_q_heads).total) +
+           align_up((size_t)2 * shape->batch * shape->n_q_heads * sizeof(int32_t), 256);
   return SP_OK;
 }
 
@@ -1941,6 +2046,152 @@ sp_status sp_prefill_layer_gated(const sp_shape *shape, const void *q, const voi
                       workspace_bytes, hip_stream);
 }
 
+
+sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                const int32_t *head_to_cluster, float gamma, float delta, float tau,
+                                int32_t score_mode, int32_t select_mode, const sp_pattern_dict *dict, void *o,
+                                float *block_scores, int32_t *role, float *a_hat, float *dist, void *workspace,
+                                size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k")) || (rc = check_ptr16(v, "v")) ||
+      (rc = check_ptr16(o, "o")))
+    return rc;
+  if (!head_to_cluster || !dict || !block_scores || !role || !a_hat || !dist) {
+    set_err("head_to_cluster / dict / block_scores / role / a_hat / dist must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (dict->n_clusters <= 0 || !dict->valid || !dict->a_tilde || !dict->kb_idx || !dict->kb_cnt) {
+    set_err("dict: n_clusters must be positive and valid / a_tilde / kb_idx / kb_cnt non-NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((score_mode != SP_SCORE_BLOCK_MASS && score_mode != SP_SCORE_MEAN_LOGIT) ||
+      (select_mode != SP_SELECT_PER_ROW && select_mode != SP_SELECT_GLOBAL)) {
+    set_err("unknown score_mode %d / select_mode %d", score_mode, select_mode);
+    return SP_ERR_INVALID_ARG;
+  }
+  if (!(gamma > 0.f) || gamma > 1.f) {
+    set_err("gamma %g outside (0, 1]", (double)gamma);
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((rc = check_thresholds(delta, tau))) return rc;
+  const int Hq = shape->n_q_heads, nqb = shape->seq / shape->block;
+  if ((int64_t)shape->batch * dict->n_clusters > 65535) {
+    set_err("batch * dict clusters exceeds 65535");
+    return SP_ERR_UNSUPPORTED;
+  }
+  ElectParams ep;
+  memset(&ep, 0, sizeof(ep));
+  int n_slots = 0;
+  for (int hq = 0; hq < Hq; ++hq) {
+    const int c = head_to_cluster[hq];
+    if (c < -1 || c >= dict->n_clusters) {
+      set_err("head_to_cluster[%d] = %d outside [-1, %d)", hq, c, dict->n_clusters);
+      return SP_ERR_INVALID_ARG;
+    }
+    ep.head_cluster[hq] = c;
+    ep.head_slot[hq] = -1;
+  }
+  // slots = the distinct clusters of this layer, ascending: each may elect one pivot here
+  for (int c = 0; c < dict->n_clusters; ++c) {
+    bool used = false;
+    for (int hq = 0; hq < Hq; ++hq)
+      if (head_to_cluster[hq] == c) {
+        used = true;
+        ep.head_slot[hq] = n_slots;
+      }
+    if (used) ep.slot_cluster[n_slots++] = c;
+  }
+  const bool mass = score_mode == SP_SCORE_BLOCK_MASS;
+  const PatternLayout PG = pattern_layout(shape, Hq);
+  const size_t off_lws = pack_bytes(shape);
+  const size_t off_pat = off_lws + (mass ? lws_bytes(shape, n_slots) : 0);
+  const size_t off_tab = off_pat + PG.total;
+  const size_t need = off_tab + align_up((size_t)2 * shape->batch * Hq * sizeof(int32_t), 256);
+  if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char *ws = (char *)workspace;
+  int32_t *pivot_head = (int32_t *)(ws + off_tab);
+  int32_t *route = pivot_head + (size_t)shape->batch * Hq;
+
+  if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
+  // 1. Alg. 3: every head's last-row estimate, then roles (election / sharing / fallback) on the device
+  int32_t all[SP_MAX_HEADS];
+  for (int hq = 0; hq < Hq; ++hq) all[hq] = hq;
+  if ((rc = launch_mean_logit_scores(shape, q, k, all, Hq, nqb - 1, 1, a_hat, ws + off_pat, st))) return rc;
+  ep.a_hat = a_hat;
+  ep.dist = dist;
+  ep.role = role;
+  ep.pivot_head = pivot_head;
+  ep.route = route;
+  ep.valid = dict->valid;
+  ep.a_tilde = dict->a_tilde;
+  ep.nkb = nqb;
+  ep.n_q_heads = Hq;
+  ep.n_slots = n_slots;
+  ep.n_clusters = dict->n_clusters;
+  ep.delta = delta;
+  ep.tau = tau;
+  {
+    ProfScope prof(KK_SCORE, st);
+    hipLaunchKernelGGL(elect_kernel, dim3(shape->batch), dim3(1024), 0, st, ep);
+    if ((rc = hip_check(hipGetLastError(), "elect_kernel launch"))) return rc;
+  }
+  AttnParams ap;
+  HeadList hl;
+  if (n_slots) {
+    // 2. elected pivots: dense attention (Alg. 4: no pattern yet => all ones) + their block score map;
+    //    one listed position per slot, its head read on the device, empty positions exit at once
+    fill_attn(ap, shape, q, workspace, o);
+    hl.n = n_slots;
+    for (int s2 = 0; s2 < n_slots; ++s2) hl.head[s2] = 0;
+    ap.head_dev = pivot_head;
+    ap.n_q_heads = Hq;
+    if (mass) {
+      ap.lws = (float *)(ws + off_lws);
+      ap.scores = block_scores;
+    }
+    if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
+    if (!mass && (rc = launch_mean_logit_scores(shape, q, k, nullptr, n_slots, 0, nqb, block_scores, ws + off_pat, st,
+                                                pivot_head)))
+      return rc;
+    // 3. Alg. 2 for the elected slots, written straight into the dictionary
+    if (select_mode == SP_SELECT_PER_ROW)
+      rc = launch_mask(block_scores, shape->batch * n_slots, nqb, nqb, gamma, dict->kb_idx, dict->kb_cnt, nullptr, st,
+                       route);
+    else
+      rc = launch_mask_global(block_scores, shape->batch * n_slots, nqb, gamma, 1, dict->kb_idx, dict->kb_cnt,
+                              ws + off_pat + PG.gsel, st, route);
+    if (rc) return rc;
+  }
+  // 4. heads outside every cluster: dense, no scores
+  fill_attn(ap, shape, q, workspace, o);
+  hl.n = 0;
+  for (int hq = 0; hq < Hq; ++hq)
+    if (head_to_cluster[hq] < 0) hl.head[hl.n++] = hq;
+  if (hl.n) {
+    if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
+  }
+  // 5. clustered heads by role: shared -> the dictionary's lists, fallback -> dense, pivot -> done above
+  fill_attn(ap, shape, q, workspace, o);
+  hl.n = 0;
+  for (int hq = 0; hq < Hq; ++hq)
+    if (head_to_cluster[hq] >= 0) {
+      hl.head[hl.n] = hq;
+      hl.map[hl.n] = head_to_cluster[hq];
+      ++hl.n;
+    }
+  if (hl.n) {
+    ap.n_maps = dict->n_clusters;
+    ap.kb_idx = dict->kb_idx;
+    ap.kb_cnt = dict->kb_cnt;
+    ap.head_pattern = role;
+    ap.n_q_heads = Hq;
+    if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
+  }
+  return SP_OK;
+}
 
 sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
                            const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,

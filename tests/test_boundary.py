@@ -44,8 +44,9 @@ def test_workspace_bytes_and_shape_validation():
     assert sp.sp_score_workspace_bytes(s, 2) == score_ws(2)
     assert sp.sp_mask_workspace_bytes(2, 16) == mask_ws(2)
     # the attention calls' workspace also covers the gate, which pools all 4 heads
-    assert sp.sp_workspace_bytes(s, 0) == pack + score_ws(4) + mask_ws(4)
-    assert sp.sp_workspace_bytes(s, 2) == pack + 2 * 16 * 16 * 64 * 4 + score_ws(4) + mask_ws(4)
+    tables = 256        # elected pivots and list routing of the dictionary call, 2 x batch x heads int32
+    assert sp.sp_workspace_bytes(s, 0) == pack + score_ws(4) + mask_ws(4) + tables
+    assert sp.sp_workspace_bytes(s, 2) == pack + 2 * 16 * 16 * 64 * 4 + score_ws(4) + mask_ws(4) + tables
     with pytest.raises(sp.SpError):
         sp.sp_mask_workspace_bytes(0, 16)
     with pytest.raises(sp.SpError):
@@ -149,6 +150,21 @@ def test_calls_reject_bad_arguments_without_launching():
                                   ctypes.c_float(0.3), ctypes.c_float(0.2), 0, 0, fake, fake, fake, fake, fake, None,
                                   fake, fake, 1 << 30, None)
     assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"dist" in L.sp_last_error()
+    # dictionary call
+    d = sp.SpPatternDict()
+    d.n_clusters, d.valid, d.a_tilde, d.kb_idx, d.kb_cnt = 2, 4096, 4096, 4096, 4096
+    args = lambda dd, hc, ws_bytes: (ctypes.byref(s), fake, fake, fake, hc, ctypes.c_float(0.9), ctypes.c_float(0.3),
+                                     ctypes.c_float(0.2), 0, 0, dd, fake, fake, fake, fake, fake, fake, ws_bytes, None)
+    rc = L.sp_prefill_layer_dict(*args(None, h2c, 1 << 30))
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    bad_c = (ctypes.c_int32 * 4)(0, 0, 1, 2)          # cluster 2 does not exist in a 2-cluster dictionary
+    rc = L.sp_prefill_layer_dict(*args(ctypes.byref(d), bad_c, 1 << 30))
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"head_to_cluster[3]" in L.sp_last_error()
+    rc = L.sp_prefill_layer_dict(*args(ctypes.byref(d), h2c, 64))
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    d.kb_cnt = None
+    rc = L.sp_prefill_layer_dict(*args(ctypes.byref(d), h2c, 1 << 30))
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"dict" in L.sp_last_error()
 
 
 def test_generator_is_deterministic_and_bf16_round_trip():
