@@ -34,6 +34,83 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {"llama8b_128k": 16.93e9}
 
 
+def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
+    """L layers of one prompt through the dictionary; a "step" is the whole stack of layers."""
+    nl = args.dict_layers
+    delta, tau = (float(x) for x in (args.gate or "10,0.2").split(","))
+    score_mode = sp.SP_SCORE_MEAN_LOGIT if args.score_mode == "mean-logit" else sp.SP_SCORE_BLOCK_MASS
+    select_mode = sp.SP_SELECT_GLOBAL if args.select_mode == "global" else sp.SP_SELECT_PER_ROW
+    t0 = time.time()
+    Ls = [make_layer(CONFIGS[args.config], layer=l, seq=args.seq, structure_layer=0) for l in range(nl)]
+    gen_s = time.time() - t0
+    cfg = Ls[0]["cfg"]
+    B, d, N, Hq, C = cfg.block, cfg.head_dim, cfg.seq, cfg.n_q_heads, cfg.n_clusters
+    nqb = N // B
+    dev = [{x: torch.from_numpy(L[x].view(np.int16)).view(torch.bfloat16).unsqueeze(0).cuda() for x in "qkv"} for L in Ls]
+    h2c = [int(x) for x in Ls[0]["head_to_cluster"]]
+    shape = sp.shape_of(dev[0]["q"], dev[0]["k"], None, B)
+    outs = [torch.zeros_like(dv["q"]) for dv in dev]
+    ws = torch.empty(sp.sp_workspace_bytes(shape, C), dtype=torch.uint8, device="cuda")
+    scores = torch.empty((1, C, nqb, nqb), dtype=torch.float32, device="cuda")
+    valid = torch.zeros((1, C), dtype=torch.int32, device="cuda")
+    a_tilde = torch.empty((1, C, nqb), dtype=torch.float32, device="cuda")
+    kb_idx = torch.empty((1, C, nqb, nqb), dtype=torch.int32, device="cuda")
+    kb_cnt = torch.empty((1, C, nqb), dtype=torch.int32, device="cuda")
+    pd = sp.pattern_dict_of(valid, a_tilde, kb_idx, kb_cnt)
+    roles = [torch.empty((1, Hq), dtype=torch.int32, device="cuda") for _ in range(nl)]
+    a_hat = torch.empty((1, Hq, nqb), dtype=torch.float32, device="cuda")
+    dist = torch.empty((1, Hq, 2), dtype=torch.float32, device="cuda")
+
+    def step():
+        valid.zero_()                      # a new prefill starts with an empty dictionary
+        for l in range(nl):
+            sp.sp_prefill_layer_dict(shape, dev[l]["q"], dev[l]["k"], dev[l]["v"], h2c, cfg.gamma, delta, tau,
+                                     score_mode, select_mode, pd, outs[l], scores, roles[l], a_hat, dist, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sp.sp_profile_enable(True)
+    sp.sp_profile_read(reset=True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = sp.sp_profile_read(reset=True)
+    sp.sp_profile_enable(False)
+    ms_step = wall * 1e3 / args.steps
+    role_h = [r.cpu().numpy()[0] for r in roles]
+    cnt = kb_cnt.cpu().numpy()[0].astype(np.int64)
+    tile_flops = 4.0 * B * B * d
+    dense_tiles_per_head = nqb * (nqb + 1) // 2
+    tiles = 0
+    for r in role_h:
+        for h in range(Hq):
+            tiles += int(cnt[r[h]].sum()) if r[h] >= 0 else dense_tiles_per_head
+    dense_equiv_flops = nl * Hq * 4.0 * d * (N * (N + 1) / 2.0)
+    out = {
+        "metric": "sparse-prefill attention ms/layer at 128K + effective TFLOP/s vs dense",
+        "value": dense_equiv_flops / (ms_step * 1e-3) / 1e12,
+        "unit": "effective TFLOP/s (dense-causal-equivalent flops / sparse-prefill layer time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {nl} layers of one prompt through the cross-layer pattern dictionary, "
+                               f"batch 1, {Hq}q/{cfg.n_kv_heads}kv heads, d{d}, seq {N}, block {B}, {C} clusters spanning "
+                               f"the layers, gamma {cfg.gamma}, delta {delta}, tau {tau}",
+                   "density": float(cnt.sum() / (C * dense_tiles_per_head))},
+        "ms_per_layer": ms_step / nl,
+        "computed_tflops": tiles * tile_flops / (ms_step * 1e-3) / 1e12,
+        "roles_per_layer": [{"pivot": int((r == -2).sum()), "shared": int((r >= 0).sum()),
+                             "fallback": int((r == -1).sum())} for r in role_h],
+        "kernel_ms_per_step": {kk: prof[kk][0] / args.steps for kk in prof},
+        "pattern": {"score_mode": args.score_mode, "select_mode": args.select_mode},
+        "input_gen_s": gen_s,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +125,9 @@ def main() -> int:
                     help="Alg. 2 per query-block row (default) or once over the flattened map as printed")
     ap.add_argument("--gate", default=None, metavar="DELTA,TAU",
                     help="run Alg. 3's gate in front of the sharing (sp_prefill_layer_gated), e.g. 0.3,0.2")
+    ap.add_argument("--dict-layers", type=int, default=0, metavar="L",
+                    help="time L layers of one prompt through the cross-layer pattern dictionary "
+                         "(sp_prefill_layer_dict; thresholds from --gate, default 10,0.2) and print that line instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-all", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -64,6 +144,8 @@ def main() -> int:
     from synth import CONFIGS, make_layer
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.dict_layers > 0:
+        return bench_dict(args, sp, torch, np, CONFIGS, make_layer)
     t0 = time.time()
     L = make_layer(CONFIGS[args.config], layer=args.layer, seq=args.seq)
     cfg = L["cfg"]
