@@ -20,6 +20,9 @@ Stages (one attention head at a time, arrays are float32 ``[N][d]``):
                       Alg. 3 (Determine Sparse Pattern): the last query block's
                       block-averaged attention estimate, its Jensen-Shannon distances to
                       the uniform distribution and to the pivot's representative, the gate
+* ``vertical_slash_sums``, ``select_cumulative``, ``vs_block_lists``, ``vertical_slash_pattern``
+                      Alg. 5 (Search Vertical Slash Pattern): vertical / slash sums of the last
+                      query block's attention, the two cumulative selections, the block lists
 * ``prefill_layers_dict`` Alg. 1 head by head, layer by layer, with the dynamic pivotal
                       pattern dictionary (Sec. 5.2): first qualifying head of a cluster runs
                       dense and installs the pattern, later heads, in this or later layers, share it
@@ -74,6 +77,13 @@ def _load():
         L.spo_build_mask_global.restype = ctypes.c_int
         L.spo_build_mask_global.argtypes = [fp, ctypes.c_int, ctypes.c_float, ctypes.c_int, ip, ip,
                                             ctypes.POINTER(ctypes.c_int64)]
+        up = ctypes.POINTER(ctypes.c_ubyte)
+        L.spo_vertical_slash_sums.restype = ctypes.c_int
+        L.spo_vertical_slash_sums.argtypes = [fp, fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, fp, fp]
+        L.spo_select_cumulative.restype = ctypes.c_int
+        L.spo_select_cumulative.argtypes = [fp, ctypes.c_int64, ctypes.c_float, up, ctypes.POINTER(ctypes.c_int64)]
+        L.spo_vs_block_lists.restype = ctypes.c_int
+        L.spo_vs_block_lists.argtypes = [up, up, ctypes.c_int, ctypes.c_int, ctypes.c_int, ip, ip]
         L.spo_js_distance.restype = ctypes.c_int
         L.spo_js_distance.argtypes = [fp, fp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
         _lib = L
@@ -242,9 +252,63 @@ def determine_pattern(a_hat, a_tilde, delta: float, tau: float):
     return (d_sparse < delta) and (d_sim < tau), d_sparse, d_sim
 
 
+def vertical_slash_sums(q, k, n_hat: int, scale: Optional[float] = None):
+    """Alg. 5: normalised vertical sums a_v [N] and slash sums a_s [N] of the causal attention of the last
+    n_hat queries."""
+    q, qp = _f(q)
+    k, kp = _f(k)
+    N, d = q.shape
+    scale = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    a_v = np.empty(N, dtype=np.float32)
+    a_s = np.empty(N, dtype=np.float32)
+    fp = ctypes.POINTER(ctypes.c_float)
+    rc = _load().spo_vertical_slash_sums(qp, kp, N, d, n_hat, scale, a_v.ctypes.data_as(fp), a_s.ctypes.data_as(fp))
+    if rc:
+        raise ValueError(f"spo_vertical_slash_sums failed ({rc})")
+    return a_v, a_s
+
+
+def select_cumulative(v, gamma: float):
+    """Shortest descending prefix (ties: lower index) whose sum reaches gamma of the total: (keep uint8 [n], K)."""
+    v, vp = _f(v)
+    keep = np.zeros(v.shape[0], dtype=np.uint8)
+    K = ctypes.c_int64(0)
+    rc = _load().spo_select_cumulative(vp, v.shape[0], ctypes.c_float(np.float32(gamma)),
+                                       keep.ctypes.data_as(ctypes.POINTER(ctypes.c_ubyte)), ctypes.byref(K))
+    if rc:
+        raise ValueError(f"spo_select_cumulative failed ({rc})")
+    return keep, int(K.value)
+
+
+def vs_block_lists(keep_v, keep_s, block: int, forced: bool = True):
+    """Block lists (kb_idx [nkb][nkb], kb_cnt [nkb]) of the vertical-slash pattern with those kept keys / offsets."""
+    keep_v = np.ascontiguousarray(keep_v, dtype=np.uint8)
+    keep_s = np.ascontiguousarray(keep_s, dtype=np.uint8)
+    N = keep_v.shape[0]
+    assert keep_s.shape == (N,)
+    nkb = N // block
+    idx = np.empty((nkb, nkb), dtype=np.int32)
+    cnt = np.empty((nkb,), dtype=np.int32)
+    up, ip = ctypes.POINTER(ctypes.c_ubyte), ctypes.POINTER(ctypes.c_int32)
+    rc = _load().spo_vs_block_lists(keep_v.ctypes.data_as(up), keep_s.ctypes.data_as(up), N, block,
+                                    int(bool(forced)), idx.ctypes.data_as(ip), cnt.ctypes.data_as(ip))
+    if rc:
+        raise ValueError(f"spo_vs_block_lists failed ({rc})")
+    return idx, cnt
+
+
+def vertical_slash_pattern(q, k, block: int, gamma: float, scale: Optional[float] = None, forced: bool = True):
+    """Alg. 5 for one head with Q_hat = the last `block` queries.  Returns (kb_idx, kb_cnt, a_v, a_s, keep_v, keep_s)."""
+    a_v, a_s = vertical_slash_sums(q, k, block, scale)
+    keep_v, _ = select_cumulative(a_v, gamma)
+    keep_s, _ = select_cumulative(a_s, gamma)
+    idx, cnt = vs_block_lists(keep_v, keep_s, block, forced)
+    return idx, cnt, a_v, a_s, keep_v, keep_s
+
+
 def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: float,
                   rows: Optional[Sequence[int]] = None, scale: Optional[float] = None,
-                  masks=None, paper_pattern: bool = False, gate=None, shared=None):
+                  masks=None, paper_pattern: bool = False, gate=None, shared=None, fallback: str = "dense"):
     """One layer of pattern sharing with given pivots (Alg. 1 / Alg. 2 / Alg. 4).
 
     q [N][Hq][d], k/v [N][Hkv][d] float32.  Returns a dict with
@@ -260,7 +324,9 @@ def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: floa
     every clustered non-pivot head, the pivot's own estimate serving as the pivotal
     representative: heads that fail run dense (the stand-in for the fallback pattern);
     the result then also holds "shared" [Hq] bool and "dist" [Hq][2].  `shared`, if
-    given, replaces the gate's decisions (to check outputs under decisions taken elsewhere)."""
+    given, replaces the gate's decisions (to check outputs under decisions taken elsewhere).
+    `fallback` = "vertical_slash" gives failing heads and heads without a cluster the
+    pattern of Alg. 5 instead of dense attention (needs every row)."""
     q = np.asarray(q, dtype=np.float32)
     k = np.asarray(k, dtype=np.float32)
     v = np.asarray(v, dtype=np.float32)
@@ -312,7 +378,11 @@ def prefill_layer(q, k, v, block: int, head_to_cluster, pivot_heads, gamma: floa
             continue
         c = int(head_to_cluster[h])
         g = h // G
-        if c < 0 or not decided[h]:
+        if (c < 0 or not decided[h]) and fallback == "vertical_slash":
+            assert nr == nkb, "the vertical-slash lists are built for every row"
+            vi, vc = vertical_slash_pattern(q[:, h], k[:, g], block, gamma, scale)[:2]
+            o[:, h] = masked_rows(q[:, h], k[:, g], v[:, g], block, vi, vc, rows, scale)
+        elif c < 0 or not decided[h]:
             o[:, h], _, _ = dense_rows(q[:, h], k[:, g], v[:, g], block, rows, scale, want_scores=False)
         else:
             o[:, h] = masked_rows(q[:, h], k[:, g], v[:, g], block, kb_idx[c], kb_cnt[c], rows, scale)
@@ -323,7 +393,7 @@ ROLE_FALLBACK, ROLE_PIVOT = -1, -2
 
 
 def prefill_layers_dict(layers, block: int, gamma: float, delta: float, tau: float, paper_pattern: bool = False,
-                        scale: Optional[float] = None, pattern_dict: Optional[dict] = None):
+                        scale: Optional[float] = None, pattern_dict: Optional[dict] = None, fallback: str = "dense"):
     """Alg. 1 applied head by head (ascending head index), layer by layer, with the pivotal pattern
     dictionary of Sec. 5.2 carried across layers.
 
@@ -333,8 +403,9 @@ def prefill_layers_dict(layers, block: int, gamma: float, delta: float, tau: flo
       shared_pivot and an entry exists  -> masked attention with the entry's lists (Alg. 4), role c;
       shared_pivot and no entry         -> dense attention (all-ones pattern), then Alg. 2 builds the
                                            lists and the entry (a~ = this head's estimate), role -2;
-      otherwise                          -> the fallback pattern (dense here), role -1, no update.
-    Heads without a cluster run dense (role -1).  Every row of every map is needed.
+      otherwise                          -> the fallback pattern, role -1, no update: dense attention,
+                                           or with fallback = "vertical_slash" the pattern of Alg. 5.
+    Heads without a cluster take the fallback too (role -1).  Every row of every map is needed.
 
     Returns (results, pattern_dict): results[l] = {"o", "role" [Hq], "dist" [Hq][2]};
     pattern_dict[c] = {"a_tilde", "kb_idx", "kb_cnt", "scores", "layer", "head"}."""
@@ -371,6 +442,9 @@ def prefill_layers_dict(layers, block: int, gamma: float, delta: float, tau: flo
                     idx, cnt, _ = build_mask_rows(sc, gamma)
                 D[c] = {"a_tilde": a_hat, "kb_idx": idx, "kb_cnt": cnt, "scores": sc, "layer": l, "head": h}
                 role[h] = ROLE_PIVOT
+            elif fallback == "vertical_slash":
+                vi, vc = vertical_slash_pattern(qh, kh, block, gamma, scale)[:2]
+                o[:, h] = masked_rows(qh, kh, vh, block, vi, vc, None, scale)
             else:
                 o[:, h], _, _ = dense_rows(qh, kh, vh, block, None, scale, want_scores=False)
         results.append({"o": o, "role": role, "dist": dist})

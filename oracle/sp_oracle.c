@@ -452,3 +452,121 @@ int spo_js_distance(const float *p, const float *q, int n, double *out) {
   *out = sqrt(jsd > 0.0 ? jsd : 0.0);
   return 0;
 }
+
+/* ==== Search Vertical Slash Pattern (Alg. 5) ================================
+ *
+ *   A_hat    = causal softmax of the scaled logits of the last n_hat queries
+ *              (the representative subset Q_hat) against every key.
+ *   a_v[s]   = sum over those queries of A_hat[t][s]          ("vertical" sums)
+ *   a_s[o]   = sum over those queries of A_hat[t][t - o]      ("slash" sums, o = t - s >= 0)
+ *              both divided by the total of A_hat (= n_hat: every row sums to 1).
+ *   select   each vector is sorted descending (ties: lower index first) and the
+ *              shortest prefix whose sum reaches gamma of the vector's total is kept,
+ *              in the same exact 24-bit fixed point as the block selections above.
+ *   pattern  token (t, s), s <= t, is attended iff key s is a kept vertical or
+ *              offset t - s a kept slash.  A key block j of query block i is kept
+ *              iff it contains at least one such (t, s); attention then runs over
+ *              whole blocks (a superset of the token pattern).
+ */
+int spo_vertical_slash_sums(const float *q, const float *k, int N, int d, int n_hat, double scale, float *a_v,
+                            float *a_s) {
+  if (N <= 0 || d <= 0 || n_hat <= 0 || n_hat > N) return 1;
+  double *av = (double *)calloc((size_t)N, sizeof(double));
+  double *as = (double *)calloc((size_t)N, sizeof(double));
+  double *x = (double *)malloc(sizeof(double) * (size_t)N);
+  if (!av || !as || !x) {
+    free(av);
+    free(as);
+    free(x);
+    return 2;
+  }
+  for (int t = N - n_hat; t < N; ++t) {
+    const double mx = logits_row(q, k, t, d, scale, x);
+    double den = 0.0;
+    for (int s = 0; s <= t; ++s) {
+      x[s] = exp(x[s] - mx);
+      den += x[s];
+    }
+    for (int s = 0; s <= t; ++s) {
+      const double p = x[s] / den;
+      av[s] += p;
+      as[t - s] += p;
+    }
+  }
+  for (int s = 0; s < N; ++s) {
+    a_v[s] = (float)(av[s] / (double)n_hat);
+    a_s[s] = (float)(as[s] / (double)n_hat);
+  }
+  free(av);
+  free(as);
+  free(x);
+  return 0;
+}
+
+typedef struct {
+  uint32_t u;
+  int64_t f;
+} spo_vkey;
+static int vkey_cmp(const void *a, const void *b) {
+  const spo_vkey *x = (const spo_vkey *)a, *y = (const spo_vkey *)b;
+  if (x->u != y->u) return (x->u > y->u) ? -1 : 1;
+  return (x->f < y->f) ? -1 : (x->f > y->f);
+}
+
+/* keep[j] = 1 for the shortest descending prefix of v[0..n) whose sum reaches gamma of the total */
+int spo_select_cumulative(const float *v, int64_t n, float gamma, unsigned char *keep, int64_t *K_out) {
+  if (n <= 0 || !(gamma > 0.0f) || gamma > 1.0f) return 1;
+  const uint64_t gq = (uint64_t)rintf(gamma * 16777216.0f);
+  spo_vkey *keys = (spo_vkey *)malloc(sizeof(spo_vkey) * (size_t)n);
+  if (!keys) return 2;
+  unsigned __int128 tot = 0;
+  for (int64_t j = 0; j < n; ++j) {
+    keys[j].u = quantise(v[j]);
+    keys[j].f = j;
+    tot += keys[j].u;
+    keep[j] = 0;
+  }
+  qsort(keys, (size_t)n, sizeof(spo_vkey), vkey_cmp);
+  int64_t K = 0;
+  if (tot > 0) {
+    unsigned __int128 cum = 0;
+    for (int64_t kk = 0; kk < n; ++kk) {
+      cum += keys[kk].u;
+      if ((cum << 24) >= (unsigned __int128)gq * tot) {
+        K = kk + 1;
+        break;
+      }
+    }
+  }
+  for (int64_t kk = 0; kk < K; ++kk) keep[keys[kk].f] = 1;
+  if (K_out) *K_out = K;
+  free(keys);
+  return 0;
+}
+
+/*
+ * Block lists of a vertical-slash pattern.  keep_v / keep_s [N]: kept keys / kept offsets.
+ * Block (i, j), j <= i, is kept iff some token pair (t, s) inside it with s <= t has
+ * keep_v[s] or keep_s[t - s]: any kept key in block j, or any kept offset among the
+ * offsets the block's pairs realise, max(0, (i-j)B - (B-1)) .. (i-j)B + (B-1).
+ * forced != 0 adds the sink block 0 and the diagonal block i to every row.
+ */
+int spo_vs_block_lists(const unsigned char *keep_v, const unsigned char *keep_s, int N, int B, int forced,
+                       int32_t *kb_idx, int32_t *kb_cnt) {
+  if (N <= 0 || B <= 0 || N % B) return 1;
+  const int nkb = N / B;
+  for (int i = 0; i < nkb; ++i) {
+    int c = 0;
+    for (int j = 0; j <= i; ++j) {
+      int on = forced && (j == 0 || j == i);
+      for (int s = j * B; s < (j + 1) * B && !on; ++s) on = keep_v[s];
+      const int lo = (i - j) * B - (B - 1) < 0 ? 0 : (i - j) * B - (B - 1);
+      const int hi = (i - j) * B + (B - 1);
+      for (int o = lo; o <= hi && o < N && !on; ++o) on = keep_s[o];
+      if (on) kb_idx[(size_t)i * nkb + c++] = j;
+    }
+    kb_cnt[i] = c;
+    for (; c < nkb; ++c) kb_idx[(size_t)i * nkb + c] = -1;
+  }
+  return 0;
+}
