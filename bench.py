@@ -50,7 +50,11 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
     h2c = [int(x) for x in Ls[0]["head_to_cluster"]]
     shape = sp.shape_of(dev[0]["q"], dev[0]["k"], None, B)
     outs = [torch.zeros_like(dv["q"]) for dv in dev]
-    ws = torch.empty(sp.sp_workspace_bytes(shape, C), dtype=torch.uint8, device="cuda")
+    vs = args.fallback == "vs"
+    ws = torch.empty(sp.sp_workspace_bytes(shape, C) + (sp.sp_vs_workspace_bytes(shape, Hq) if vs else 0),
+                     dtype=torch.uint8, device="cuda")
+    vs_idx = torch.empty((1, Hq, nqb, nqb), dtype=torch.int32, device="cuda") if vs else None
+    vs_cnt = torch.zeros((1, Hq, nqb), dtype=torch.int32, device="cuda") if vs else None
     scores = torch.empty((1, C, nqb, nqb), dtype=torch.float32, device="cuda")
     valid = torch.zeros((1, C), dtype=torch.int32, device="cuda")
     a_tilde = torch.empty((1, C, nqb), dtype=torch.float32, device="cuda")
@@ -65,7 +69,9 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
         valid.zero_()                      # a new prefill starts with an empty dictionary
         for l in range(nl):
             sp.sp_prefill_layer_dict(shape, dev[l]["q"], dev[l]["k"], dev[l]["v"], h2c, cfg.gamma, delta, tau,
-                                     score_mode, select_mode, pd, outs[l], scores, roles[l], a_hat, dist, ws)
+                                     score_mode, select_mode, pd, outs[l], scores, roles[l], a_hat, dist, ws,
+                                     fallback_mode=sp.SP_FALLBACK_VERTICAL_SLASH if vs else sp.SP_FALLBACK_DENSE,
+                                     vs_idx=vs_idx, vs_cnt=vs_cnt)
 
     for _ in range(args.warmup):
         step()
@@ -85,9 +91,17 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
     tile_flops = 4.0 * B * B * d
     dense_tiles_per_head = nqb * (nqb + 1) // 2
     tiles = 0
-    for r in role_h:
+    vs_last = vs_cnt.cpu().numpy()[0].astype(np.int64) if vs else None   # lists of the last layer's fallback heads
+    for l, r in enumerate(role_h):
         for h in range(Hq):
-            tiles += int(cnt[r[h]].sum()) if r[h] >= 0 else dense_tiles_per_head
+            if r[h] >= 0:
+                tiles += int(cnt[r[h]].sum())
+            elif r[h] == -1 and vs and l == nl - 1:
+                tiles += int(vs_last[h].sum())
+            elif r[h] == -1 and vs:
+                tiles += -1 << 60        # unknown for earlier layers (their lists were overwritten): flagged below
+            else:
+                tiles += dense_tiles_per_head
     dense_equiv_flops = nl * Hq * 4.0 * d * (N * (N + 1) / 2.0)
     out = {
         "metric": "sparse-prefill attention ms/layer at 128K + effective TFLOP/s vs dense",
@@ -100,7 +114,11 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
                                f"the layers, gamma {cfg.gamma}, delta {delta}, tau {tau}",
                    "density": float(cnt.sum() / (C * dense_tiles_per_head))},
         "ms_per_layer": ms_step / nl,
-        "computed_tflops": tiles * tile_flops / (ms_step * 1e-3) / 1e12,
+        "computed_tflops": tiles * tile_flops / (ms_step * 1e-3) / 1e12 if tiles >= 0 else None,
+        "fallback": args.fallback,
+        "vs_block_density_last_layer": (float(sum(vs_last[h].sum() for h in range(Hq) if role_h[-1][h] == -1)
+                                              / max(1, int((role_h[-1] == -1).sum()) * dense_tiles_per_head))
+                                        if vs else None),
         "roles_per_layer": [{"pivot": int((r == -2).sum()), "shared": int((r >= 0).sum()),
                              "fallback": int((r == -1).sum())} for r in role_h],
         "kernel_ms_per_step": {kk: prof[kk][0] / args.steps for kk in prof},
@@ -128,6 +146,8 @@ def main() -> int:
     ap.add_argument("--dict-layers", type=int, default=0, metavar="L",
                     help="time L layers of one prompt through the cross-layer pattern dictionary "
                          "(sp_prefill_layer_dict; thresholds from --gate, default 10,0.2) and print that line instead")
+    ap.add_argument("--fallback", choices=["dense", "vs"], default="dense",
+                    help="with --dict-layers: what heads that fail Alg. 3 run (dense, or the vertical-slash pattern of Alg. 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-all", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -62,9 +62,9 @@ const char *sp_last_error(void);
  * App. A.2 "Latency Benchmark", times whole runs).  While enabled, every kernel the calls
  * below launch is bracketed by two HIP events on the caller's stream.  After the caller has
  * synchronised that stream, sp_profile_read sums elapsed milliseconds and launch counts per
- * kernel kind into host arrays ms[5] / launches[5]: 0 = K/V packing, 1 = dense attention
+ * kernel kind into host arrays ms[6] / launches[6]: 0 = K/V packing, 1 = dense attention
  * (+ block-mass scores), 2 = mask builder, 3 = block-sparse attention, 4 = block-mean-logit
- * scores; `reset` != 0 drops the records.
+ * scores and the Alg. 3 gate, 5 = vertical-slash search; `reset` != 0 drops the records.
  * Process-wide and not thread-safe.
  */
 sp_status sp_profile_enable(int32_t on);
@@ -259,6 +259,34 @@ sp_status sp_prefill_layer_gated(const sp_shape *shape, const void *q, const voi
                                  float *block_scores, int32_t *kb_idx, int32_t *kb_cnt, float *a_hat, float *dist,
                                  int32_t *head_pattern, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* What a head does when Alg. 3 sends it to the fallback pattern. */
+enum { SP_FALLBACK_DENSE = 0,            /* dense causal attention (exact) */
+       SP_FALLBACK_VERTICAL_SLASH = 1 }; /* the pattern of Alg. 5 */
+
+/* Workspace of sp_search_vertical_slash for n_heads listed heads (block * seq * 4 bytes per head and more). */
+sp_status sp_vs_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *bytes);
+
+/*
+ * Alg. 5 (Search Vertical Slash Pattern) for the listed heads, with Q_hat = the last `block`
+ * queries: A_hat = causal softmax of their scaled logits against every key;
+ *   a_v[s] = sum_t A_hat[t][s] / sum(A_hat),  a_s[o] = sum_t A_hat[t][t-o] / sum(A_hat);
+ * each vector is quantised to 24 bits as in sp_build_block_mask, ordered by (value descending,
+ * index ascending) and cut at the shortest prefix whose sum reaches gamma of its total; a token
+ * pair (t, s), s <= t, belongs to the pattern iff key s or offset t-s is kept.  The result is
+ * returned at block granularity: key block j is listed for query block i iff the block holds at
+ * least one pair of the pattern (attention over the lists covers a superset of the token
+ * pattern); `forced` != 0 adds the sink block 0 and the diagonal block i to every row.
+ *   head_ids host [n_heads] distinct query heads
+ *   sums     device fp32 [batch][n_heads][2][seq] or NULL  (output: a_v then a_s)
+ *   kb_idx   device int32 [batch][n_heads][nqb][nkb]       (output, ascending, tail -1)
+ *   kb_cnt   device int32 [batch][n_heads][nqb]            (output)
+ *   workspace sp_vs_workspace_bytes(shape, n_heads)
+ * Feed the lists to sp_block_sparse_attn with head_map[n] = n and n_maps = n_heads.
+ */
+sp_status sp_search_vertical_slash(const sp_shape *shape, const void *q, const void *k, const int32_t *head_ids,
+                                   int32_t n_heads, float gamma, int32_t forced, float *sums, int32_t *kb_idx,
+                                   int32_t *kb_cnt, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /*
  * The dynamic pivotal pattern dictionary (Sec. 5.2, "Dynamic Pattern Construction and Sharing
  * during Inference"): for every cluster of the offline head dictionary, the pattern its first
@@ -284,9 +312,11 @@ typedef struct {
  *     its score map becomes the entry's pattern (Alg. 2 per score_mode / select_mode as in
  *     sp_prefill_layer_modes) and its estimate the entry's a~; the heads after it are tested
  *     against that estimate; heads before it, and all heads if none qualifies, fall back.
- *   Heads with cluster -1 and fallback heads run dense attention (the stand-in for Alg. 5) and
- *   never touch the dictionary.  Everything is decided on the device: one stream, no host
- *   synchronisation; the roles can be read back afterwards.
+ *   Heads with cluster -1 and fallback heads (role -1) never touch the dictionary; with
+ *   fallback_mode SP_FALLBACK_DENSE they run dense attention, with SP_FALLBACK_VERTICAL_SLASH
+ *   each gets its own pattern from Alg. 5 (sp_search_vertical_slash with the layer's gamma, forced
+ *   blocks on) and runs block-sparse over it.  Everything is decided on the device: one stream, no
+ *   host synchronisation; the roles can be read back afterwards.
  *   head_to_cluster host [n_q_heads] global cluster id in [0, dict->n_clusters) or -1
  *   block_scores    device fp32 [batch][n_slots][nqb][nkb], n_slots = number of distinct clusters
  *                   in head_to_cluster (ascending cluster id); slot s is written only if its
@@ -294,13 +324,18 @@ typedef struct {
  *   role            device int32 [batch][n_q_heads]      (output)
  *   a_hat, dist     device fp32 [batch][n_q_heads][nkb] / [batch][n_q_heads][2]   (outputs, Alg. 3; heads
  *                   without a cluster get their estimate and d_sparse too, with d_sim = 0)
- *   workspace       sp_workspace_bytes(shape, n_slots)
+ *   vs_idx, vs_cnt  device int32 [batch][n_q_heads][nqb][nkb] / [batch][n_q_heads][nqb]: the lists of
+ *                   the heads that took the vertical-slash fallback (other heads' entries are left
+ *                   untouched); may be NULL with SP_FALLBACK_DENSE
+ *   workspace       sp_workspace_bytes(shape, n_slots), plus sp_vs_workspace_bytes(shape, n_q_heads)
+ *                   with SP_FALLBACK_VERTICAL_SLASH
  */
 sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void *k, const void *v,
                                 const int32_t *head_to_cluster, float gamma, float delta, float tau,
-                                int32_t score_mode, int32_t select_mode, const sp_pattern_dict *dict, void *o,
-                                float *block_scores, int32_t *role, float *a_hat, float *dist, void *workspace,
-                                size_t workspace_bytes, void *hip_stream);
+                                int32_t score_mode, int32_t select_mode, int32_t fallback_mode,
+                                const sp_pattern_dict *dict, void *o, float *block_scores, int32_t *role, float *a_hat,
+                                float *dist, int32_t *vs_idx, int32_t *vs_cnt, void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
 
 #ifdef __cplusplus
 }

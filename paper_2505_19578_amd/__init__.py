@@ -13,6 +13,7 @@ from .binding import (SpError, SpShape, lib, shape_of, sp_workspace_bytes, sp_pr
                       sp_build_block_mask_global, sp_prefill_layer_modes,
                       sp_determine_pattern, sp_block_sparse_attn_gated, sp_prefill_layer_gated,
                       sp_prefill_layer_dict, pattern_dict_of, SpPatternDict,
+                      sp_vs_workspace_bytes, sp_search_vertical_slash, SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH,
                       SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT, SP_SELECT_PER_ROW, SP_SELECT_GLOBAL)
 
 __all__ = ["SpError", "SpShape", "lib", "shape_of", "sp_workspace_bytes", "sp_profile_enable", "sp_profile_read",
@@ -22,4 +23,5 @@ __all__ = ["SpError", "SpShape", "lib", "shape_of", "sp_workspace_bytes", "sp_pr
            "sp_build_block_mask_global", "sp_prefill_layer_modes",
            "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated",
            "sp_prefill_layer_dict", "pattern_dict_of", "SpPatternDict",
+           "sp_vs_workspace_bytes", "sp_search_vertical_slash", "SP_FALLBACK_DENSE", "SP_FALLBACK_VERTICAL_SLASH",
            "SP_SCORE_BLOCK_MASS", "SP_SCORE_MEAN_LOGIT", "SP_SELECT_PER_ROW", "SP_SELECT_GLOBAL"]

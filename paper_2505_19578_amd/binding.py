@@ -18,7 +18,10 @@ EXPORTED_SYMBOLS = [
     "sp_score_workspace_bytes", "sp_mask_workspace_bytes", "sp_block_mean_logit_scores",
     "sp_build_block_mask_global", "sp_prefill_layer_modes",
     "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated", "sp_prefill_layer_dict",
+    "sp_vs_workspace_bytes", "sp_search_vertical_slash",
 ]
+
+SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH = 0, 1
 
 SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT = 0, 1
 SP_SELECT_PER_ROW, SP_SELECT_GLOBAL = 0, 1
@@ -107,8 +110,14 @@ def lib() -> ctypes.CDLL:
                                              vp, vp, ctypes.c_size_t, vp]
         L.sp_prefill_layer_dict.restype = ctypes.c_int
         L.sp_prefill_layer_dict.argtypes = [sp, vp, vp, vp, ip, ctypes.c_float, ctypes.c_float, ctypes.c_float,
-                                            ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(SpPatternDict), vp, fp,
-                                            vp, fp, fp, vp, ctypes.c_size_t, vp]
+                                            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                            ctypes.POINTER(SpPatternDict), vp, fp, vp, fp, fp, vp, vp, vp,
+                                            ctypes.c_size_t, vp]
+        L.sp_vs_workspace_bytes.restype = ctypes.c_int
+        L.sp_vs_workspace_bytes.argtypes = [sp, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
+        L.sp_search_vertical_slash.restype = ctypes.c_int
+        L.sp_search_vertical_slash.argtypes = [sp, vp, vp, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_int32, fp, vp,
+                                               vp, vp, ctypes.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -148,7 +157,7 @@ def shape_of(q, k, o=None, block: int = 128, softmax_scale: float = 0.0) -> SpSh
     return s
 
 
-KERNEL_KINDS = ("pack", "dense", "mask", "sparse", "score")
+KERNEL_KINDS = ("pack", "dense", "mask", "sparse", "score", "vs")
 
 
 def sp_profile_enable(on: bool):
@@ -271,9 +280,22 @@ def pattern_dict_of(valid, a_tilde, kb_idx, kb_cnt) -> SpPatternDict:
 
 def sp_prefill_layer_dict(shape: SpShape, q, k, v, head_to_cluster, gamma: float, delta: float, tau: float,
                           score_mode: int, select_mode: int, pattern_dict: SpPatternDict, o, block_scores, role,
-                          a_hat, dist, workspace):
+                          a_hat, dist, workspace, fallback_mode: int = 0, vs_idx=None, vs_cnt=None):
     _check(lib().sp_prefill_layer_dict(
         ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_to_cluster), ctypes.c_float(gamma),
-        ctypes.c_float(delta), ctypes.c_float(tau), int(score_mode), int(select_mode), ctypes.byref(pattern_dict),
-        _ptr(o), _ptr(block_scores), _ptr(role), _ptr(a_hat), _ptr(dist), _ptr(workspace), _nbytes(workspace),
-        _stream()))
+        ctypes.c_float(delta), ctypes.c_float(tau), int(score_mode), int(select_mode), int(fallback_mode),
+        ctypes.byref(pattern_dict), _ptr(o), _ptr(block_scores), _ptr(role), _ptr(a_hat), _ptr(dist), _ptr(vs_idx),
+        _ptr(vs_cnt), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def sp_vs_workspace_bytes(shape: SpShape, n_heads: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().sp_vs_workspace_bytes(ctypes.byref(shape), n_heads, ctypes.byref(n)))
+    return int(n.value)
+
+
+def sp_search_vertical_slash(shape: SpShape, q, k, head_ids, gamma: float, forced: bool, sums, kb_idx, kb_cnt,
+                             workspace):
+    _check(lib().sp_search_vertical_slash(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ids(head_ids), len(head_ids), ctypes.c_float(gamma),
+        1 if forced else 0, _ptr(sums), _ptr(kb_idx), _ptr(kb_cnt), _ptr(workspace), _nbytes(workspace), _stream()))

@@ -52,7 +52,7 @@ thread_local char g_err[512] = "";
 
 // Optional per-kernel timing (sp_profile_enable / sp_profile_read): every launch is bracketed
 // by two HIP events on the caller's stream.  Process-wide, not thread-safe; meant for benches.
-enum KernelKind { KK_PACK = 0, KK_DENSE = 1, KK_MASK = 2, KK_SPARSE = 3, KK_SCORE = 4, KK_COUNT = 5 };
+enum KernelKind { KK_PACK = 0, KK_DENSE = 1, KK_MASK = 2, KK_SPARSE = 3, KK_SCORE = 4, KK_VS = 5, KK_COUNT = 6 };
 struct ProfRec {
   int kind;
   hipEvent_t e0, e1;
@@ -163,6 +163,9 @@ struct AttnParams {
   // a list index in [0, n_maps), or < 0 = no shared pattern, the head walks every key block 0..i
   const int32_t *head_pattern;  // [b][n_q_heads]; <= -2 = nothing to do for this head in this launch
   int n_q_heads;
+  // optional: private lists per (batch entry, query head), used by a head whose head_pattern entry is -1
+  // (its vertical-slash pattern) instead of the dense walk: [b][n_q_heads][nqb][nkb] / [b][n_q_heads][nqb]
+  const int32_t *priv_idx, *priv_cnt;
   // optional: the query head of listed position n, chosen on the device (pivot election): [b][n_heads],
   // negative = this position is empty
   const int32_t *head_dev;
@@ -293,7 +296,12 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
       map = map >= p.n_maps ? p.n_maps - 1 : map;
       if (map <= -2) return;
     }
-    if (map < 0) {
+    if (map < 0 && p.priv_idx) {
+      const int64_t lrow_id = ((int64_t)b * p.n_q_heads + head) * p.nqb + i;
+      nblk = p.priv_cnt[lrow_id];
+      nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
+      list = p.priv_idx + lrow_id * nkb;
+    } else if (map < 0) {
       nblk = i + 1;  // list stays null: dense walk
     } else {
       const int64_t lrow_id = ((int64_t)b * p.n_maps + map) * p.nqb + i;
@@ -1023,8 +1031,20 @@ struct GselView {
   GselState *state;
   uint32_t *row_ties, *row_before;
 };
-__host__ __device__ inline size_t gsel_map_bytes(int nqb) {
-  return (size_t)2 * GS_BINS * 8 + sizeof(GselState) + (((size_t)nqb * 8 + 255) / 256) * 256;
+// Shape of the maps a selection runs over.  A causal block map is n x n with only j <= row present; a plain
+// vector of length n_rows * n_cols is a rectangular map whose row-major order is the vector's order.
+struct GselGeom {
+  int n_rows, n_cols;
+  int tri;              // 1: entries j <= row only; 0: all n_cols entries of a row
+  const int32_t *role;  // optional [n_maps / per_head]: a map is processed only if its owner's entry is -1
+  int per_head;
+};
+__device__ __forceinline__ int gsel_width(const GselGeom &g, int row) { return g.tri ? row + 1 : g.n_cols; }
+__device__ __forceinline__ bool gsel_skip(const GselGeom &g, int map) {
+  return g.role != nullptr && g.role[map / g.per_head] != -1;
+}
+__host__ __device__ inline size_t gsel_map_bytes(int n_rows) {
+  return (size_t)2 * GS_BINS * 8 + sizeof(GselState) + (((size_t)n_rows * 8 + 255) / 256) * 256;
 }
 __device__ __forceinline__ GselView gsel_view(char *scratch, int map, int nqb) {
   char *base = scratch + (size_t)map * gsel_map_bytes(nqb);
@@ -1037,24 +1057,26 @@ __device__ __forceinline__ GselView gsel_view(char *scratch, int map, int nqb) {
   return v;
 }
 
-__global__ __launch_bounds__(256) void gsel_zero_kernel(char *scratch, int nqb) {
-  GselView v = gsel_view(scratch, blockIdx.x, nqb);
+__global__ __launch_bounds__(256) void gsel_zero_kernel(char *scratch, GselGeom g) {
+  GselView v = gsel_view(scratch, blockIdx.x, g.n_rows);
   for (int x = threadIdx.x; x < 2 * GS_BINS; x += 256) v.hist1[x] = 0ull;
 }
 
 template <int PASS>
-__global__ __launch_bounds__(256) void gsel_hist_kernel(const float *__restrict__ scores, int nqb, char *scratch) {
+__global__ __launch_bounds__(256) void gsel_hist_kernel(const float *__restrict__ scores, GselGeom g, char *scratch) {
   __shared__ unsigned long long h[GS_BINS];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int map = blockIdx.y;
-  GselView v = gsel_view(scratch, map, nqb);
+  if (gsel_skip(g, map)) return;
+  GselView v = gsel_view(scratch, map, g.n_rows);
   for (int x = tid; x < GS_BINS; x += 256) h[x] = 0ull;
   __syncthreads();
   const uint32_t bin_hi = (PASS == 2) ? v.state->bin_hi : 0u;
   unsigned long long low = 0ull;  // first pass: bin 0 holds most of a softmaxed map; keep it out of the LDS atomics
-  for (int row = blockIdx.x * 4 + w; row < nqb; row += gridDim.x * 4) {
-    const float *src = scores + ((int64_t)map * nqb + row) * nqb;
-    for (int j = lane; j <= row; j += 64) {
+  for (int row = blockIdx.x * 4 + w; row < g.n_rows; row += gridDim.x * 4) {
+    const float *src = scores + ((int64_t)map * g.n_rows + row) * g.n_cols;
+    const int width = gsel_width(g, row);
+    for (int j = lane; j < width; j += 64) {
       const uint32_t u = quantise24(src[j]);
       if (PASS == 1) {
         const uint32_t bin = u >> 12;
@@ -1072,18 +1094,19 @@ __global__ __launch_bounds__(256) void gsel_hist_kernel(const float *__restrict_
     if (lane == 0 && low) atomicAdd(&h[0], low);
   }
   __syncthreads();
-  unsigned long long *g = (PASS == 1) ? v.hist1 : v.hist2;
+  unsigned long long *gh = (PASS == 1) ? v.hist1 : v.hist2;
   for (int x = tid; x < GS_BINS; x += 256)
-    if (h[x]) atomicAdd(&g[x], h[x]);
+    if (h[x]) atomicAdd(&gh[x], h[x]);
 }
 
 // One workgroup of 1024 threads per map.  Thread t owns bins [5t, 5t+5); a suffix sum over threads
 // locates the bin in which the running sum from the top first reaches the target.
 template <int PASS>
-__global__ __launch_bounds__(1024) void gsel_scan_kernel(char *scratch, int nqb, uint32_t gq) {
+__global__ __launch_bounds__(1024) void gsel_scan_kernel(char *scratch, GselGeom g, uint32_t gq) {
   __shared__ unsigned long long wt[16];
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  GselView v = gsel_view(scratch, blockIdx.x, nqb);
+  if (gsel_skip(g, blockIdx.x)) return;
+  GselView v = gsel_view(scratch, blockIdx.x, g.n_rows);
   const unsigned long long *hist = (PASS == 1) ? v.hist1 : v.hist2;
   constexpr int NB = (PASS == 1) ? 4097 : 4096;
   unsigned long long mine[5], sum = 0ull;
@@ -1148,24 +1171,27 @@ __global__ __launch_bounds__(1024) void gsel_scan_kernel(char *scratch, int nqb,
   }
 }
 
-__global__ __launch_bounds__(256) void gsel_row_ties_kernel(const float *__restrict__ scores, int nqb, char *scratch) {
+__global__ __launch_bounds__(256) void gsel_row_ties_kernel(const float *__restrict__ scores, GselGeom g, char *scratch) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
-  if (row >= nqb) return;
-  GselView v = gsel_view(scratch, map, nqb);
+  if (row >= g.n_rows || gsel_skip(g, map)) return;
+  GselView v = gsel_view(scratch, map, g.n_rows);
   const uint32_t vstar = v.state->vstar;
-  const float *src = scores + ((int64_t)map * nqb + row) * nqb;
+  const float *src = scores + ((int64_t)map * g.n_rows + row) * g.n_cols;
+  const int width = gsel_width(g, row);
   uint32_t n = 0;
-  for (int j = lane; j <= row; j += 64) n += (quantise24(src[j]) == vstar) ? 1u : 0u;
+  for (int j = lane; j < width; j += 64) n += (quantise24(src[j]) == vstar) ? 1u : 0u;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) n += __shfl_xor(n, off, 64);
   if (lane == 0) v.row_ties[row] = n;
 }
 
 // exclusive prefix sum of row_ties over the rows of one map (flat order = row-major)
-__global__ __launch_bounds__(1024) void gsel_row_scan_kernel(int nqb, char *scratch) {
+__global__ __launch_bounds__(1024) void gsel_row_scan_kernel(GselGeom g, char *scratch) {
   __shared__ uint32_t wt[16];
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  if (gsel_skip(g, blockIdx.x)) return;
+  const int nqb = g.n_rows;
   GselView v = gsel_view(scratch, blockIdx.x, nqb);
   const int per = (nqb + 1023) / 1024;
   const int r0 = t * per, r1 = min(r0 + per, nqb);
@@ -1188,11 +1214,12 @@ __global__ __launch_bounds__(1024) void gsel_row_scan_kernel(int nqb, char *scra
 }
 
 // one wavefront per row: ascending list of the kept key blocks (+ sink and diagonal when forced)
-__global__ __launch_bounds__(256) void gsel_emit_kernel(const float *__restrict__ scores, int nqb, char *scratch,
+__global__ __launch_bounds__(256) void gsel_emit_kernel(const float *__restrict__ scores, GselGeom g, char *scratch,
                                                         int forced, int32_t *__restrict__ kb_idx,
                                                         int32_t *__restrict__ kb_cnt,
                                                         const int32_t *__restrict__ route) {
   const int lane = threadIdx.x & 63;
+  const int nqb = g.n_rows;
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
   if (i >= nqb) return;
   int omap = map;
@@ -1223,6 +1250,180 @@ __global__ __launch_bounds__(256) void gsel_emit_kernel(const float *__restrict_
   }
   for (int pos = n_out + lane; pos < nqb; pos += 64) out[pos] = -1;
   if (lane == 0) kb_cnt[(int64_t)omap * nqb + i] = (int32_t)n_out;
+}
+
+// Selection over plain vectors (rectangular geometry): per (map, row) two flags instead of a list:
+// bit 0 = some entry of the row is kept, bit 1 = some entry other than the row's first is kept.
+__global__ __launch_bounds__(256) void gsel_emit_flags_kernel(const float *__restrict__ scores, GselGeom g, char *scratch,
+                                                              int32_t *__restrict__ flags) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
+  if (row >= g.n_rows || gsel_skip(g, map)) return;
+  GselView v = gsel_view(scratch, map, g.n_rows);
+  const uint32_t vstar = v.state->vstar;
+  const uint64_t need = v.state->need;
+  const uint64_t before = v.row_before[row];
+  const float *src = scores + ((int64_t)map * g.n_rows + row) * g.n_cols;
+  const int width = gsel_width(g, row);
+  const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  uint32_t ties_seen = 0;
+  int any = 0, any_after_first = 0;
+  for (int j0 = 0; j0 < width; j0 += 64) {
+    const int j = j0 + lane;
+    const uint32_t x = (j < width) ? quantise24(src[j]) : 0u;
+    const bool tie = (j < width) && (x == vstar);
+    const uint64_t tmask = __ballot(tie);
+    const uint64_t trank = before + ties_seen + __popcll(tmask & lt);
+    ties_seen += __popcll(tmask);
+    const bool sel = (j < width) && ((x > vstar && vstar != 0xFFFFFFFFu) || (tie && trank < need));
+    const uint64_t smask = __ballot(sel);
+    any |= smask != 0ull;
+    any_after_first |= (j0 == 0 ? (smask & ~1ull) : smask) != 0ull;
+  }
+  if (lane == 0) flags[(int64_t)map * g.n_rows + row] = any | (any_after_first << 1);
+}
+
+// ---- Search Vertical Slash Pattern (Alg. 5) ------------------------------------------------------
+// Q_hat = the last `block` queries.  Their raw dot products with every key go to a workspace slab
+// X[b][n][t][s] (fp32), three memory-bound passes turn it into the normalised vertical sums a_v[s] and
+// slash sums a_s[t - s], the vector selection above keeps the shortest prefixes reaching gamma, and the kept
+// keys / offsets become per-row key-block lists.
+struct VsParams {
+  const uint16_t *q, *k;
+  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
+  int seq, group, n_heads, n_q_heads;
+  float c;               // softmax scale * log2(e)
+  float *x;              // [b][n][B][seq]
+  float *stats;          // [b][n][B][2]  row max (log2 domain) and 1 / row sum
+  float *sums;           // [b][n][2][seq] a_v then a_s
+  const int32_t *role;   // optional [b][n_q_heads]: only heads whose entry is -1 are processed
+  int32_t head_ids[SP_MAX_HEADS];
+};
+__device__ __forceinline__ bool vs_skip(const VsParams &p, int b, int n) {
+  return p.role != nullptr && p.role[(int64_t)b * p.n_q_heads + p.head_ids[n]] != -1;
+}
+
+// X = Q_hat K^T with the queries as MFMA rows and the keys as columns, so that one accumulator register
+// holds 32 consecutive keys of one query across the lanes and the stores coalesce.  A workgroup takes 128
+// keys (32 per wavefront) against all B queries; operands come straight from the caller's Q and K.
+template <int D, int B>
+__global__ __launch_bounds__(256) void vs_logits_kernel(VsParams p) {
+  constexpr int DS = D / 16;
+  const int n = blockIdx.y, b = blockIdx.z;
+  if (vs_skip(p, b, n)) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, c = lane & 31;
+  const int head = p.head_ids[n];
+  const int s0 = blockIdx.x * 128 + 32 * w;
+  const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)(s0 + c) * p.k_st + (int64_t)(head / p.group) * p.k_sh + 8 * h;
+  bf16x8 kf[DS];
+#pragma unroll
+  for (int ds = 0; ds < DS; ++ds) kf[ds] = *reinterpret_cast<const bf16x8 *>(kp + 16 * ds);
+  float *xo = p.x + (((int64_t)b * p.n_heads + n) * B) * p.seq + s0 + c;
+#pragma unroll
+  for (int qt = 0; qt < B / 32; ++qt) {
+    const uint16_t *qp = p.q + (int64_t)b * p.q_sb + (int64_t)(p.seq - B + 32 * qt + c) * p.q_st +
+                         (int64_t)head * p.q_sh + 8 * h;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) {
+      const bf16x8 qf = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ds], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int t = 32 * qt + 8 * (r >> 2) + 4 * h + (r & 3);
+      xo[(int64_t)t * p.seq] = acc[r];
+    }
+  }
+}
+
+// causal softmax statistics of each of the B query rows: one workgroup per row
+template <int B>
+__global__ __launch_bounds__(256) void vs_rowstats_kernel(VsParams p) {
+  __shared__ float red[4];
+  const int t = blockIdx.x, n = blockIdx.y, b = blockIdx.z;
+  if (vs_skip(p, b, n)) return;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int last = p.seq - B + t;  // keys 0 .. last exist for this query
+  const float *x = p.x + (((int64_t)b * p.n_heads + n) * B + t) * p.seq;
+  float mx = -INFINITY;
+  for (int s = tid; s <= last; s += 256) mx = fmaxf(mx, x[s]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  if (lane == 0) red[w] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])) * p.c;
+  __syncthreads();
+  float sum = 0.f;
+  for (int s = tid; s <= last; s += 256) sum += fast_exp2(__builtin_fmaf(x[s], p.c, -mx));
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+  if (lane == 0) red[w] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    float *st = p.stats + (((int64_t)b * p.n_heads + n) * B + t) * 2;
+    st[0] = mx;
+    st[1] = 1.f / (red[0] + red[1] + red[2] + red[3]);
+  }
+}
+
+// thread i owns key i (vertical sum) and offset i (slash sum); the B queries are added in a fixed order
+template <int B>
+__global__ __launch_bounds__(256) void vs_sums_kernel(VsParams p) {
+  __shared__ float st[B][2];
+  const int n = blockIdx.y, b = blockIdx.z;
+  if (vs_skip(p, b, n)) return;
+  const int64_t hb = (int64_t)b * p.n_heads + n;
+  for (int x = threadIdx.x; x < 2 * B; x += 256) st[x >> 1][x & 1] = p.stats[hb * B * 2 + x];
+  __syncthreads();
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= p.seq) return;
+  const float *x = p.x + hb * B * p.seq;
+  const int t0 = p.seq - B;
+  float av = 0.f, as = 0.f;
+  for (int t = 0; t < B; ++t) {
+    const int tabs = t0 + t;
+    if (i <= tabs) {
+      av += fast_exp2(__builtin_fmaf(x[(int64_t)t * p.seq + i], p.c, -st[t][0])) * st[t][1];
+      as += fast_exp2(__builtin_fmaf(x[(int64_t)t * p.seq + (tabs - i)], p.c, -st[t][0])) * st[t][1];
+    }
+  }
+  p.sums[(hb * 2) * p.seq + i] = av * (1.f / B);
+  p.sums[(hb * 2 + 1) * p.seq + i] = as * (1.f / B);
+}
+
+// Kept keys / offsets -> key-block lists.  flags[b][n][2][nkb] come from the vector selection with rows of
+// `block` entries: bit 0 = a kept entry in the row, bit 1 = a kept entry other than the row's first.  Block
+// (i, j) holds a kept key iff row j of the vertical flags has bit 0; its token pairs realise the offsets
+// (i-j)B - (B-1) .. (i-j)B + (B-1): all of slash row i-j, and slash row i-j-1 without its first entry.
+__global__ __launch_bounds__(256) void vs_block_lists_kernel(VsParams p, const int32_t *__restrict__ flags, int nkb,
+                                                             int forced, int by_head, int32_t *__restrict__ kb_idx,
+                                                             int32_t *__restrict__ kb_cnt) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), n = blockIdx.y, b = blockIdx.z;
+  if (i >= nkb || vs_skip(p, b, n)) return;
+  const int head = p.head_ids[n], n_heads = p.n_heads, n_q_heads = p.n_q_heads;
+  const int32_t *fv = flags + (((int64_t)b * n_heads + n) * 2) * nkb, *fs = fv + nkb;
+  // lists are stored per listed position, or per query head when they serve a whole layer
+  const int64_t orow = (by_head ? ((int64_t)b * n_q_heads + head) : ((int64_t)b * n_heads + n)) * nkb + i;
+  int32_t *out = kb_idx + orow * nkb;
+  const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  uint32_t n_out = 0;
+  for (int j0 = 0; j0 <= i; j0 += 64) {
+    const int j = j0 + lane;
+    bool sel = false;
+    if (j <= i) {
+      const int dlt = i - j;
+      sel = (fv[j] & 1) || (fs[dlt] & 1) || (dlt >= 1 && (fs[dlt - 1] & 2)) || (forced && (j == 0 || j == i));
+    }
+    const uint64_t smask = __ballot(sel);
+    if (sel) out[n_out + __popcll(smask & lt)] = j;
+    n_out += __popcll(smask);
+  }
+  for (int pos = n_out + lane; pos < nkb; pos += 64) out[pos] = -1;
+  if (lane == 0) kb_cnt[orow] = (int32_t)n_out;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1547,12 +1748,116 @@ sp_status launch_determine(const sp_shape *s, const void *q, const void *k, cons
   return hip_check(hipGetLastError(), "js_gate_kernel launch");
 }
 
+void launch_gsel_threshold(const float *scores, int n_maps, const GselGeom &g, uint32_t gq, char *scratch,
+                           hipStream_t st);
+
+// workspace of the vertical-slash search for n listed heads per batch entry
+struct VsLayout {
+  size_t x, stats, sums, flags, gsel, total;
+};
+VsLayout vs_layout(const sp_shape *s, int n) {
+  const size_t maps = (size_t)s->batch * n, nkb = s->seq / s->block;
+  VsLayout L;
+  L.x = 0;
+  L.stats = L.x + align_up(maps * s->block * s->seq * sizeof(float), 256);
+  L.sums = L.stats + align_up(maps * s->block * 2 * sizeof(float), 256);
+  L.flags = L.sums + align_up(maps * 2 * s->seq * sizeof(float), 256);
+  L.gsel = L.flags + align_up(maps * 2 * nkb * sizeof(int32_t), 256);
+  L.total = L.gsel + align_up(maps * 2 * gsel_map_bytes((int)nkb), 256);
+  return L;
+}
+
+// Alg. 5 for the listed heads: block lists into kb_idx / kb_cnt ([b][n] or, by_head, [b][n_q_heads]).
+// role (device, [b][n_q_heads], needs the heads listed 0..n_q_heads-1) restricts the work to heads whose
+// entry is -1.  sums_out (optional, [b][n][2][seq]) receives a_v and a_s.
+sp_status launch_vertical_slash(const sp_shape *s, const void *q, const void *k, const int32_t *heads, int n,
+                                float gamma, int forced, const int32_t *role, int by_head, float *sums_out,
+                                int32_t *kb_idx, int32_t *kb_cnt, char *vs_ws, hipStream_t st) {
+  if ((int64_t)s->batch * n * 2 > 65535) {
+    set_err("batch * heads * 2 = %lld exceeds 65535", (long long)s->batch * n * 2);
+    return SP_ERR_UNSUPPORTED;
+  }
+  const VsLayout L = vs_layout(s, n);
+  const int nkb = s->seq / s->block;
+  VsParams vp;
+  memset(&vp, 0, sizeof(vp));
+  vp.q = (const uint16_t *)q;
+  vp.k = (const uint16_t *)k;
+  vp.q_sb = s->q_stride_b;
+  vp.q_st = s->q_stride_t;
+  vp.q_sh = s->q_stride_h;
+  vp.k_sb = s->kv_stride_b;
+  vp.k_st = s->kv_stride_t;
+  vp.k_sh = s->kv_stride_h;
+  vp.seq = s->seq;
+  vp.group = s->n_q_heads / s->n_kv_heads;
+  vp.n_heads = n;
+  vp.n_q_heads = s->n_q_heads;
+  const float scale = (s->softmax_scale > 0.f) ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
+  vp.c = scale * 1.4426950408889634f;
+  vp.x = (float *)(vs_ws + L.x);
+  vp.stats = (float *)(vs_ws + L.stats);
+  vp.sums = sums_out ? sums_out : (float *)(vs_ws + L.sums);
+  vp.role = role;
+  for (int a = 0; a < n; ++a) vp.head_ids[a] = heads[a];
+  int32_t *flags = (int32_t *)(vs_ws + L.flags);
+  ProfScope prof(KK_VS, st);
+  const dim3 glog(s->seq / 128, n, s->batch), gstat(s->block, n, s->batch), gsum((s->seq + 255) / 256, n, s->batch);
+#define SP_VS(D_, B_)                                                                  \
+  do {                                                                                 \
+    hipLaunchKernelGGL((vs_logits_kernel<D_, B_>), glog, dim3(256), 0, st, vp);        \
+    hipLaunchKernelGGL((vs_rowstats_kernel<B_>), gstat, dim3(256), 0, st, vp);         \
+    hipLaunchKernelGGL((vs_sums_kernel<B_>), gsum, dim3(256), 0, st, vp);              \
+  } while (0)
+  if (s->head_dim == 128 && s->block == 128)
+    SP_VS(128, 128);
+  else if (s->head_dim == 128 && s->block == 64)
+    SP_VS(128, 64);
+  else if (s->head_dim == 64 && s->block == 128)
+    SP_VS(64, 128);
+  else
+    SP_VS(64, 64);
+#undef SP_VS
+  sp_status rc = hip_check(hipGetLastError(), "vertical-slash sum kernels launch");
+  if (rc) return rc;
+  // the two selections of every head: vectors of seq entries seen as nkb rows of `block`
+  GselGeom g;
+  g.n_rows = nkb;
+  g.n_cols = s->block;
+  g.tri = 0;
+  g.role = role;
+  g.per_head = 2;
+  const int n_maps = s->batch * n * 2;
+  const uint32_t gq = (uint32_t)rintf(gamma * 16777216.f);
+  launch_gsel_threshold(vp.sums, n_maps, g, gq, vs_ws + L.gsel, st);
+  hipLaunchKernelGGL(gsel_emit_flags_kernel, dim3((nkb + 3) / 4, n_maps), dim3(256), 0, st, vp.sums, g,
+                     vs_ws + L.gsel, flags);
+  hipLaunchKernelGGL(vs_block_lists_kernel, dim3((nkb + 3) / 4, n, s->batch), dim3(256), 0, st, vp, flags, nkb, forced,
+                     by_head, kb_idx, kb_cnt);
+  return hip_check(hipGetLastError(), "vertical-slash selection kernels launch");
+}
+
 sp_status check_thresholds(float delta, float tau) {
   if (!(delta >= 0.f) || !(tau >= 0.f) || std::isinf(delta) || std::isinf(tau)) {
     set_err("delta %g / tau %g must be finite and >= 0", (double)delta, (double)tau);
     return SP_ERR_INVALID_ARG;
   }
   return SP_OK;
+}
+
+// the seven launches that leave, per map, the threshold value, the number of ties to take and every
+// row's tie count prefix in the selection scratch
+void launch_gsel_threshold(const float *scores, int n_maps, const GselGeom &g, uint32_t gq, char *scratch,
+                           hipStream_t st) {
+  const int row_groups = (g.n_rows + 3) / 4;
+  const dim3 ghist(std::min(row_groups, 64), n_maps), grows(row_groups, n_maps);
+  hipLaunchKernelGGL(gsel_zero_kernel, dim3(n_maps), dim3(256), 0, st, scratch, g);
+  hipLaunchKernelGGL(gsel_hist_kernel<1>, ghist, dim3(256), 0, st, scores, g, scratch);
+  hipLaunchKernelGGL(gsel_scan_kernel<1>, dim3(n_maps), dim3(1024), 0, st, scratch, g, gq);
+  hipLaunchKernelGGL(gsel_hist_kernel<2>, ghist, dim3(256), 0, st, scores, g, scratch);
+  hipLaunchKernelGGL(gsel_scan_kernel<2>, dim3(n_maps), dim3(1024), 0, st, scratch, g, gq);
+  hipLaunchKernelGGL(gsel_row_ties_kernel, grows, dim3(256), 0, st, scores, g, scratch);
+  hipLaunchKernelGGL(gsel_row_scan_kernel, dim3(n_maps), dim3(1024), 0, st, g, scratch);
 }
 
 // Alg. 2 over each flattened map; `scratch` holds n_maps * gsel_map_bytes(nqb) bytes
@@ -1566,14 +1871,14 @@ sp_status launch_mask_global(const float *scores, int n_maps, int nqb, float gam
   const int row_groups = (nqb + 3) / 4;
   const dim3 ghist(std::min(row_groups, 64), n_maps), grows(row_groups, n_maps);
   ProfScope prof(KK_MASK, st);
-  hipLaunchKernelGGL(gsel_zero_kernel, dim3(n_maps), dim3(256), 0, st, scratch, nqb);
-  hipLaunchKernelGGL(gsel_hist_kernel<1>, ghist, dim3(256), 0, st, scores, nqb, scratch);
-  hipLaunchKernelGGL(gsel_scan_kernel<1>, dim3(n_maps), dim3(1024), 0, st, scratch, nqb, gq);
-  hipLaunchKernelGGL(gsel_hist_kernel<2>, ghist, dim3(256), 0, st, scores, nqb, scratch);
-  hipLaunchKernelGGL(gsel_scan_kernel<2>, dim3(n_maps), dim3(1024), 0, st, scratch, nqb, gq);
-  hipLaunchKernelGGL(gsel_row_ties_kernel, grows, dim3(256), 0, st, scores, nqb, scratch);
-  hipLaunchKernelGGL(gsel_row_scan_kernel, dim3(n_maps), dim3(1024), 0, st, nqb, scratch);
-  hipLaunchKernelGGL(gsel_emit_kernel, grows, dim3(256), 0, st, scores, nqb, scratch, forced, kb_idx, kb_cnt, route);
+  GselGeom g;
+  g.n_rows = nqb;
+  g.n_cols = nqb;
+  g.tri = 1;
+  g.role = nullptr;
+  g.per_head = 1;
+  launch_gsel_threshold(scores, n_maps, g, gq, scratch, st);
+  hipLaunchKernelGGL(gsel_emit_kernel, grows, dim3(256), 0, st, scores, g, scratch, forced, kb_idx, kb_cnt, route);
   return hip_check(hipGetLastError(), "global selection kernels launch");
 }
 
@@ -2049,9 +2354,10 @@ sp_status sp_prefill_layer_gated(const sp_shape *shape, const void *q, const voi
 
 sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void *k, const void *v,
                                 const int32_t *head_to_cluster, float gamma, float delta, float tau,
-                                int32_t score_mode, int32_t select_mode, const sp_pattern_dict *dict, void *o,
-                                float *block_scores, int32_t *role, float *a_hat, float *dist, void *workspace,
-                                size_t workspace_bytes, void *hip_stream) {
+                                int32_t score_mode, int32_t select_mode, int32_t fallback_mode,
+                                const sp_pattern_dict *dict, void *o, float *block_scores, int32_t *role, float *a_hat,
+                                float *dist, int32_t *vs_idx, int32_t *vs_cnt, void *workspace, size_t workspace_bytes,
+                                void *hip_stream) {
   g_err[0] = 0;
   sp_status rc = check_shape(shape);
   if (rc) return rc;
@@ -2076,6 +2382,15 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
     return SP_ERR_INVALID_ARG;
   }
   if ((rc = check_thresholds(delta, tau))) return rc;
+  if (fallback_mode != SP_FALLBACK_DENSE && fallback_mode != SP_FALLBACK_VERTICAL_SLASH) {
+    set_err("unknown fallback_mode %d", fallback_mode);
+    return SP_ERR_INVALID_ARG;
+  }
+  const bool vs = fallback_mode == SP_FALLBACK_VERTICAL_SLASH;
+  if (vs && (!vs_idx || !vs_cnt)) {
+    set_err("vs_idx / vs_cnt must not be NULL with the vertical-slash fallback");
+    return SP_ERR_INVALID_ARG;
+  }
   const int Hq = shape->n_q_heads, nqb = shape->seq / shape->block;
   if ((int64_t)shape->batch * dict->n_clusters > 65535) {
     set_err("batch * dict clusters exceeds 65535");
@@ -2108,7 +2423,8 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
   const size_t off_lws = pack_bytes(shape);
   const size_t off_pat = off_lws + (mass ? lws_bytes(shape, n_slots) : 0);
   const size_t off_tab = off_pat + PG.total;
-  const size_t need = off_tab + align_up((size_t)2 * shape->batch * Hq * sizeof(int32_t), 256);
+  const size_t off_vs = off_tab + align_up((size_t)2 * shape->batch * Hq * sizeof(int32_t), 256);
+  const size_t need = off_vs + (vs ? vs_layout(shape, Hq).total : 0);
   if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   char *ws = (char *)workspace;
@@ -2165,21 +2481,28 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
                               ws + off_pat + PG.gsel, st, route);
     if (rc) return rc;
   }
-  // 4. heads outside every cluster: dense, no scores
-  fill_attn(ap, shape, q, workspace, o);
-  hl.n = 0;
-  for (int hq = 0; hq < Hq; ++hq)
-    if (head_to_cluster[hq] < 0) hl.head[hl.n++] = hq;
-  if (hl.n) {
-    if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
+  if (vs) {
+    // 4. Alg. 5 for every head whose role is -1 (fallback and heads outside every cluster), lists per head
+    if ((rc = launch_vertical_slash(shape, q, k, all, Hq, gamma, 1, role, 1, nullptr, vs_idx, vs_cnt, ws + off_vs, st)))
+      return rc;
+  } else {
+    // 4. heads outside every cluster: dense, no scores
+    fill_attn(ap, shape, q, workspace, o);
+    hl.n = 0;
+    for (int hq = 0; hq < Hq; ++hq)
+      if (head_to_cluster[hq] < 0) hl.head[hl.n++] = hq;
+    if (hl.n) {
+      if ((rc = launch_attn<true>(shape, ap, hl, st))) return rc;
+    }
   }
-  // 5. clustered heads by role: shared -> the dictionary's lists, fallback -> dense, pivot -> done above
+  // 5. heads by role: shared -> the dictionary's lists, fallback -> dense or their vertical-slash lists,
+  //    pivot -> done above
   fill_attn(ap, shape, q, workspace, o);
   hl.n = 0;
   for (int hq = 0; hq < Hq; ++hq)
-    if (head_to_cluster[hq] >= 0) {
+    if (head_to_cluster[hq] >= 0 || vs) {
       hl.head[hl.n] = hq;
-      hl.map[hl.n] = head_to_cluster[hq];
+      hl.map[hl.n] = head_to_cluster[hq] >= 0 ? head_to_cluster[hq] : dict->n_clusters + hq;
       ++hl.n;
     }
   if (hl.n) {
@@ -2188,9 +2511,50 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
     ap.kb_cnt = dict->kb_cnt;
     ap.head_pattern = role;
     ap.n_q_heads = Hq;
+    if (vs) {
+      ap.priv_idx = vs_idx;
+      ap.priv_cnt = vs_cnt;
+    }
     if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
   }
   return SP_OK;
+}
+
+sp_status sp_vs_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *bytes) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if (!bytes) {
+    set_err("bytes is NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n_heads < 0 || n_heads > shape->n_q_heads) {
+    set_err("n_heads %d outside [0, %d]", n_heads, shape->n_q_heads);
+    return SP_ERR_INVALID_ARG;
+  }
+  *bytes = vs_layout(shape, n_heads).total;
+  return SP_OK;
+}
+
+sp_status sp_search_vertical_slash(const sp_shape *shape, const void *q, const void *k, const int32_t *head_ids,
+                                   int32_t n_heads, float gamma, int32_t forced, float *sums, int32_t *kb_idx,
+                                   int32_t *kb_cnt, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k"))) return rc;
+  if ((rc = check_heads(shape, head_ids, n_heads, "head_ids"))) return rc;
+  if (!kb_idx || !kb_cnt) {
+    set_err("kb_idx / kb_cnt must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (!(gamma > 0.f) || gamma > 1.f) {
+    set_err("gamma %g outside (0, 1]", (double)gamma);
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((rc = check_ws(workspace, workspace_bytes, vs_layout(shape, n_heads).total))) return rc;
+  return launch_vertical_slash(shape, q, k, head_ids, n_heads, gamma, forced != 0, nullptr, 0, sums, kb_idx, kb_cnt,
+                               (char *)workspace, (hipStream_t)hip_stream);
 }
 
 sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,

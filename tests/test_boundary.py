@@ -153,8 +153,9 @@ def test_calls_reject_bad_arguments_without_launching():
     # dictionary call
     d = sp.SpPatternDict()
     d.n_clusters, d.valid, d.a_tilde, d.kb_idx, d.kb_cnt = 2, 4096, 4096, 4096, 4096
-    args = lambda dd, hc, ws_bytes: (ctypes.byref(s), fake, fake, fake, hc, ctypes.c_float(0.9), ctypes.c_float(0.3),
-                                     ctypes.c_float(0.2), 0, 0, dd, fake, fake, fake, fake, fake, fake, ws_bytes, None)
+    args = lambda dd, hc, ws_bytes, fb=0, vsp=None: (
+        ctypes.byref(s), fake, fake, fake, hc, ctypes.c_float(0.9), ctypes.c_float(0.3), ctypes.c_float(0.2), 0, 0, fb,
+        dd, fake, fake, fake, fake, fake, vsp, vsp, fake, ws_bytes, None)
     rc = L.sp_prefill_layer_dict(*args(None, h2c, 1 << 30))
     assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
     bad_c = (ctypes.c_int32 * 4)(0, 0, 1, 2)          # cluster 2 does not exist in a 2-cluster dictionary
@@ -162,9 +163,25 @@ def test_calls_reject_bad_arguments_without_launching():
     assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"head_to_cluster[3]" in L.sp_last_error()
     rc = L.sp_prefill_layer_dict(*args(ctypes.byref(d), h2c, 64))
     assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    rc = L.sp_prefill_layer_dict(*args(ctypes.byref(d), h2c, 1 << 30, fb=1))      # vertical-slash fallback needs its lists
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"vs_idx" in L.sp_last_error()
+    rc = L.sp_prefill_layer_dict(*args(ctypes.byref(d), h2c, 1 << 30, fb=7, vsp=fake))
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"fallback_mode" in L.sp_last_error()
     d.kb_cnt = None
     rc = L.sp_prefill_layer_dict(*args(ctypes.byref(d), h2c, 1 << 30))
     assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"dict" in L.sp_last_error()
+    # Alg. 5
+    rc = L.sp_search_vertical_slash(ctypes.byref(s), fake, fake, ids, 2, ctypes.c_float(0.9), 1, None, fake, None,
+                                    fake, 1 << 40, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"kb_cnt" in L.sp_last_error()
+    rc = L.sp_search_vertical_slash(ctypes.byref(s), fake, fake, ids, 2, ctypes.c_float(0.0), 1, None, fake, fake,
+                                    fake, 1 << 40, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"gamma" in L.sp_last_error()
+    rc = L.sp_search_vertical_slash(ctypes.byref(s), fake, fake, ids, 2, ctypes.c_float(0.9), 1, None, fake, fake,
+                                    fake, 4096, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    # slab of raw logits (block x seq fp32 per head) dominates the search's workspace
+    assert sp.sp_vs_workspace_bytes(s, 2) >= 2 * 64 * 1024 * 4 + 2 * 2 * 1024 * 4
 
 
 def test_generator_is_deterministic_and_bf16_round_trip():
