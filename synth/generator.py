@@ -41,12 +41,12 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- #
-# configurations (BASELINE.json "configs", in order)
+# configurations (the benchmark workloads, in order)
 # --------------------------------------------------------------------------- #
 @dataclass(frozen=True)
 class LayerConfig:
     name: str
-    index: int            # 1-based position in the benchmark's config list
+    index: int            # 1-based position in the list of benchmark workloads
     seq: int
     n_q_heads: int
     n_kv_heads: int

@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
 times (one fused sp_prefill_layer call per layer).  The CPU oracle cannot finish a
 full 32K-128K layer in minutes, so outputs and score rows are compared on a sample
 of query-block rows (rows are independent: row i needs only Q block i and
