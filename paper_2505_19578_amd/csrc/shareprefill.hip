@@ -628,25 +628,60 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   }
 
   // ---- block-mass scores: S[i][j] = (1/B) sum_t 2^(lws[j][t] - L_t) ----
+  // Each wavefront takes 32 key blocks at a time.  Stage 1: lane <-> query, coalesced reads of the block
+  // log-sum-exps, one partial per (key block, lane) into a wavefront-private LDS tile (rows padded to 65
+  // floats).  Stage 2: lane <-> key block, the tile is read transposed and summed.  No cross-lane reduction
+  // chain and several rows of loads in flight: the workspace rows were written long ago and come from HBM.
   if (SCORES) {
+    constexpr int TPL = B / 64, PST = 65, JU = 8;
+    constexpr int JB = (1024 + NW * 32 * PST * 4 <= (RK + RV) * IMG) ? 32 : 16;  // key blocks per tile
+    constexpr int NPART = 64 / JB, PLEN = 64 / NPART;  // stage 2: NPART lanes share a key block, PLEN entries each
+    static_assert(1024 + NW * JB * PST * 4 <= (RK + RV) * IMG, "score epilogue tiles must fit the idle rings");
     float *lse_sh = reinterpret_cast<float *>(smem);  // [B]; the rings are idle now
+    float *part = reinterpret_cast<float *>(smem + 1024) + w * (JB * PST);
     __syncthreads();
     if (h == 0) lse_sh[tq] = m + fast_log2(l);
     __threadfence();
     __syncthreads();
-    {
-      const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb) * B;
-      float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb;
-      for (int j = w; j <= i; j += NW) {
-        float acc = 0.f;
+    float lt[TPL];
 #pragma unroll
-        for (int t = lane; t < B; t += 64) acc += fast_exp2(lblk[(int64_t)j * B + t] - lse_sh[t]);
+    for (int tt = 0; tt < TPL; ++tt) lt[tt] = lse_sh[lane + 64 * tt];
+    const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb) * B;
+    float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb;
+    const int jr = lane % JB, jp = lane / JB;
+    for (int j0 = w * JB; j0 <= i; j0 += NW * JB) {
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-        if (lane == 0) srow[j] = acc * (1.f / B);
+      for (int u0 = 0; u0 < JB; u0 += JU) {
+        float x[JU][TPL];
+#pragma unroll
+        for (int u = 0; u < JU; ++u) {
+          const int j = (j0 + u0 + u <= i) ? j0 + u0 + u : i;
+#pragma unroll
+          for (int tt = 0; tt < TPL; ++tt) x[u][tt] = lblk[(int64_t)j * B + lane + 64 * tt];
+        }
+#pragma unroll
+        for (int u = 0; u < JU; ++u) {
+          float e = 0.f;
+#pragma unroll
+          for (int tt = 0; tt < TPL; ++tt) e += fast_exp2(x[u][tt] - lt[tt]);
+          part[(u0 + u) * PST + lane] = e;
+        }
       }
-      for (int j = i + 1 + w * 64 + lane; j < nkb; j += NW * 64) srow[j] = 0.f;
+      // the tile is private to this wavefront: order its own LDS writes before its transposed reads
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      float acc = 0.f;
+#pragma unroll
+      for (int kq = 0; kq < PLEN; ++kq) acc += part[jr * PST + jp * PLEN + kq];
+      acc = sum_xor32(acc);
+      if (NPART == 4) acc += __shfl_xor(acc, 16, 64);
+      if (jp == 0 && j0 + jr <= i) srow[j0 + jr] = acc * (1.f / B);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
+    for (int j = i + 1 + w * 64 + lane; j < nkb; j += NW * 64) srow[j] = 0.f;
   }
 }
 
