@@ -169,3 +169,55 @@ def test_dict_llama8b_128k_three_layers_full_size():
                        label="cfg3 x3 layers")
     assert sum(1 for r in g[0]["role"] if r == -2) == 8
     assert all(r >= 0 for r in g[1]["role"]) and all(r >= 0 for r in g[2]["role"])
+
+
+def test_dict_batch_of_two_prompts_equals_two_single_runs():
+    """Batch entries are independent prefills with their own dictionaries: a batch of two prompts gives, bit for
+    bit, what each prompt gives alone (roles, dictionary, outputs), also with the vertical-slash fallback."""
+    import torch
+    import paper_2505_19578_amd as sp
+    from synth import CONFIGS, make_layer
+    from tests.gpu_util import to_dev
+    cfg = CONFIGS["tiny"]
+    B, Hq, C = cfg.block, cfg.n_q_heads, cfg.n_clusters
+    prompts = [[make_layer(cfg, layer=l, structure_layer=s0) for l in (s0, s0 + 1)] for s0 in (0, 20)]
+    nqb = prompts[0][0]["cfg"].seq // B
+    h2c = [int(x) for x in prompts[0][0]["head_to_cluster"]]
+    for fallback, delta in ((sp.SP_FALLBACK_DENSE, 10.0), (sp.SP_FALLBACK_VERTICAL_SLASH, 0.05)):
+        def run(batch_prompts):
+            nb = len(batch_prompts)
+            D = _Dict(sp, nb, C, nqb)
+            vs_idx = torch.full((nb, Hq, nqb, nqb), -3, dtype=torch.int32, device="cuda")
+            vs_cnt = torch.full((nb, Hq, nqb), -3, dtype=torch.int32, device="cuda")
+            outs = []
+            for l in range(2):
+                q, k, v = (torch.cat([to_dev(p[l][x]) for p in batch_prompts], dim=0) for x in "qkv")
+                shape = sp.shape_of(q, k, None, B)
+                ws = torch.empty(sp.sp_workspace_bytes(shape, C) + sp.sp_vs_workspace_bytes(shape, Hq),
+                                 dtype=torch.uint8, device="cuda")
+                o = torch.zeros_like(q)
+                scores = torch.zeros((nb, C, nqb, nqb), dtype=torch.float32, device="cuda")
+                role = torch.full((nb, Hq), -7, dtype=torch.int32, device="cuda")
+                a_hat = torch.empty((nb, Hq, nqb), dtype=torch.float32, device="cuda")
+                dist = torch.empty((nb, Hq, 2), dtype=torch.float32, device="cuda")
+                print(f"[dict batch {nb}] layer {l} fallback {fallback}", flush=True)
+                sp.sp_prefill_layer_dict(shape, q, k, v, h2c, cfg.gamma, delta, 10.0, 0, 0, D.c, o, scores, role, a_hat,
+                                         dist, ws, fallback_mode=fallback, vs_idx=vs_idx, vs_cnt=vs_cnt)
+                torch.cuda.synchronize()
+                outs.append((o.clone(), role.clone(), dist.clone(), a_hat.clone()))
+            return outs, D
+        both, Db = run(prompts)
+        for n, p in enumerate(prompts):
+            single, Ds = run([p])
+            for l in range(2):
+                for tb, ts in zip(both[l], single[l]):
+                    assert torch.equal(tb[n:n + 1], ts), (n, l)
+            assert torch.equal(Db.valid[n], Ds.valid[0])
+            for c in range(C):
+                if int(Ds.valid[0, c]):
+                    assert torch.equal(Db.kb_idx[n, c], Ds.kb_idx[0, c]) and torch.equal(Db.kb_cnt[n, c], Ds.kb_cnt[0, c])
+                    assert torch.equal(Db.a_tilde[n, c], Ds.a_tilde[0, c])
+        roles = both[0][1].cpu().numpy()
+        print(f"[dict batch 2] fallback {fallback}: layer-0 roles {roles.tolist()}", flush=True)
+        if fallback == sp.SP_FALLBACK_VERTICAL_SLASH:
+            assert (roles == -1).any()
