@@ -176,3 +176,57 @@ def test_run_to_run_determinism():
     for a in outs[1:]:
         for x, y in zip(outs[0], a):
             assert torch.equal(x, y)
+
+
+def test_pattern_calls_batch2_interleaved_qkv_and_custom_scale():
+    """The printed score map, Alg. 3's gate and Alg. 5's search on a batch of two prompts whose Q, K, V are
+    slices of one interleaved tensor (non-trivial strides), with a caller-given softmax scale."""
+    import torch
+    import oracle
+    import paper_2505_19578_amd as sp
+    from synth import random_qkv
+    N, Hq, Hkv, d, B, scale = 640, 4, 2, 64, 64, 0.2
+    packs = []
+    for bb in range(2):
+        q, k, v = random_qkv(70 + bb, N, Hq, Hkv, d, 1.5)
+        packs.append(np.concatenate([q, k, v], axis=1))
+    qkv = _dev(np.stack(packs))                        # [2][N][Hq+2Hkv][d]
+    q, k = qkv[:, :, :Hq], qkv[:, :, Hq:Hq + Hkv]
+    shape = sp.shape_of(q, k, None, B, softmax_scale=scale)
+    nqb = N // B
+    heads = [2, 0, 3]
+    ws = torch.empty(sp.sp_score_workspace_bytes(shape, len(heads)), dtype=torch.uint8, device="cuda")
+    sc = torch.full((2, len(heads), nqb, nqb), -1.0, dtype=torch.float32, device="cuda")
+    sp.sp_block_mean_logit_scores(shape, q, k, heads, sc, ws)
+    a_hat = torch.empty((2, len(heads), nqb), dtype=torch.float32, device="cuda")
+    dist = torch.empty((2, len(heads), 2), dtype=torch.float32, device="cuda")
+    pat = torch.full((2, Hq), -7, dtype=torch.int32, device="cuda")
+    sp.sp_determine_pattern(shape, q, k, heads, [0, 0, -1], [5, 6, 7], 10.0, 10.0, a_hat, dist, pat, ws)
+    wv = torch.empty(sp.sp_vs_workspace_bytes(shape, len(heads)), dtype=torch.uint8, device="cuda")
+    sums = torch.empty((2, len(heads), 2, N), dtype=torch.float32, device="cuda")
+    vidx = torch.empty((2, len(heads), nqb, nqb), dtype=torch.int32, device="cuda")
+    vcnt = torch.empty((2, len(heads), nqb), dtype=torch.int32, device="cuda")
+    sp.sp_search_vertical_slash(shape, q, k, heads, 0.6, True, sums, vidx, vcnt, wv)
+    torch.cuda.synchronize()
+    assert list(pat[0].cpu().numpy()) == [6, -7, 5, 7] and list(pat[1].cpu().numpy()) == [6, -7, 5, 7]
+    for bb in range(2):
+        hq, hk = _f32(packs[bb][:, :Hq]), _f32(packs[bb][:, Hq:Hq + Hkv])
+        est = []
+        for n, h in enumerate(heads):
+            want = oracle.softmax_rows(oracle.mean_logit_rows(hq[:, h], hk[:, h // 2], B, scale=scale))
+            got = sc[bb, n].cpu().numpy()
+            assert np.abs(got - want).max() <= 1e-7 + 1e-4 * want.max()
+            assert np.abs(a_hat[bb, n].cpu().numpy() - want[-1]).max() <= 1e-7 + 1e-4 * want[-1].max()
+            est.append(want[-1])
+            a_v, a_s = oracle.vertical_slash_sums(hq[:, h], hk[:, h // 2], B, scale=scale)
+            s_h = sums[bb, n].cpu().numpy()
+            assert np.abs(s_h[0] - a_v).max() <= 1e-8 + 1e-4 * a_v.max() and np.abs(s_h[1] - a_s).max() <= 1e-8 + 1e-4 * a_s.max()
+            kv, _ = oracle.select_cumulative(s_h[0], 0.6)
+            ks, _ = oracle.select_cumulative(s_h[1], 0.6)
+            i2, c2 = oracle.vs_block_lists(kv, ks, B, True)
+            assert np.array_equal(i2, vidx[bb, n].cpu().numpy()) and np.array_equal(c2, vcnt[bb, n].cpu().numpy())
+        d_h = dist[bb].cpu().numpy()
+        u = np.full(nqb, 1.0 / nqb, dtype=np.float32)
+        for n in range(len(heads)):
+            assert abs(d_h[n, 0] - oracle.js_distance(est[n], u)) <= 2e-5
+        assert abs(d_h[1, 1] - oracle.js_distance(est[1], est[0])) <= 2e-5 and d_h[0, 1] == 0.0 and d_h[2, 1] == 0.0
