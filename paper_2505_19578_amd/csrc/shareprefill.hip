@@ -238,11 +238,13 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   constexpr int STAGE = 2 * IMG;    // K image + V image in the packed buffer
   constexpr int DS = D / 16;        // k-steps of the QK^T product
   constexpr int DB = D / 32;        // 32-row blocks of O^T
-  constexpr int DK = 2, DV = 1;                              // prefetch distances (steps)
+  constexpr int DK = 2, DV = 2;                              // prefetch distances (steps)
   constexpr int RK = DK, RV = DV + 1;                        // ring slots
   constexpr int CH = IMG / 1024 / NW;                        // 1 KiB chunks per wavefront per image
-  // loads that may still be in flight at the top of a step (each step issues CH for V, then CH for K)
-  constexpr int VM_KEEP = ((2 * DV - 1) < (2 * DK - 4) ? (2 * DV - 1) : (2 * DK - 4)) * CH;
+  // Each step issues its CH chunks of K[t+DK] first, then its CH chunks of V[t+DV].  At the top of the next
+  // step K[t+1] (issued a step ago) must have landed; the V chunks issued after it are for a later step and
+  // may still be in flight (vmcnt counts in order).
+  constexpr int VM_KEEP = CH;
   static_assert(IMG % (1024 * NW) == 0, "image must split evenly over the wavefronts");
   __shared__ __attribute__((aligned(1024))) char smem[(RK + RV) * IMG];
   const uint32_t lds_k = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
@@ -434,12 +436,20 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
     wait_vm<VM_KEEP>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
     issue_img(t + DK, jk, false, lds_k + ((t + DK) % RK) * IMG);
+    issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
   };
   // fast step: tiles t and t+1 both off the diagonal.  One basic block up to the rescale test.
   auto fast_step = [&](int t, int j0, int jv, int jk, f32x16(&s_cur)[2], f32x16(&s_next)[2]) {
-    sync_and_fill(t, jv, jk);
+    // the ring refills (K for the step after next, then V for the same step) are dropped one chunk at a time
+    // into the MFMA groups below instead of going out in a burst after the barrier
+    wait_vm<VM_KEEP>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    const char *ksrc = img_src(t + DK, jk, false);
+    const uint32_t kslot = lds_k + ((t + DK) % RK) * IMG;
+    const char *vsrc = img_src(t + DV, jv, true);
+    const uint32_t vslot = lds_v + ((t + DV) % RV) * IMG;
     const char *kb = smem + ((t + 1) % RK) * IMG + lane * 16;
     const char *vb = smem + (RK + t % RV) * IMG + lane * 16;
     // Hand-laid schedule: NM groups, each = one MFMA + one LDS read (PF fragments ahead) + a slice
@@ -503,6 +513,11 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
           lval = m + fast_log2(bs);
           bs = 0.f;
         }
+      }
+      {
+        constexpr int GAP = NM / (2 * CH);  // groups between two chunk loads
+        if (n % GAP == 1 && n / GAP < CH) issue_chunk(ksrc, kslot, n / GAP);
+        if (n % GAP == 1 && n / GAP >= CH && n / GAP < 2 * CH) issue_chunk(vsrc, vslot, n / GAP - CH);
       }
       if (n >= NQ) {
         const int np = n - NQ;
