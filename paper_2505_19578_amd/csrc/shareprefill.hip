@@ -227,7 +227,7 @@ __device__ __forceinline__ void wait_vm() {
 //   interleaved instruction by instruction (a hand-laid schedule), so the softmax runs in the
 //   shadow of the matrix pipe.  Steps near the diagonal take a general path (causal mask / skip).
 // K and V images ride in LDS rings (RK, RV slots) filled by LDS-direct loads issued DK resp. DV
-// steps ahead; one workgroup barrier per step.
+// steps ahead, one chunk at a time from inside the MFMA groups; one workgroup barrier per step.
 // One query block per workgroup (B/32 wavefronts); two workgroups per CU, so each SIMD holds two
 // wavefronts of different workgroups and one's barrier / load-issue time is covered by the other.
 template <int D, int B, bool DENSE, bool SCORES>
