@@ -230,3 +230,75 @@ def test_pattern_calls_batch2_interleaved_qkv_and_custom_scale():
         for n in range(len(heads)):
             assert abs(d_h[n, 0] - oracle.js_distance(est[n], u)) <= 2e-5
         assert abs(d_h[1, 1] - oracle.js_distance(est[1], est[0])) <= 2e-5 and d_h[0, 1] == 0.0 and d_h[2, 1] == 0.0
+
+
+@pytest.mark.parametrize("N,B,d", [(128, 128, 128), (128, 64, 64), (384, 128, 64)])
+def test_shortest_sequences_through_every_layer_call(N, B, d):
+    """One, two and three query blocks: the printed construction, the gate, the dictionary over two layers and
+    the vertical-slash fallback all against the oracle's own runs (every row, every head)."""
+    import torch
+    import oracle
+    import paper_2505_19578_amd as sp
+    from synth import random_qkv
+    Hq, Hkv, gamma = 4, 2, 0.8
+    nqb = N // B
+    h2c, piv = [0, 0, 1, 1], [0, 2]
+    layers = [random_qkv(90 + l, N, Hq, Hkv, d, 1.5) for l in range(2)]
+    dev = [[_dev(x[None]) for x in L] for L in layers]
+    host = [[_f32(x) for x in L] for L in layers]
+    q, k, v = dev[0]
+    shape = sp.shape_of(q, k, None, B)
+    ws = torch.empty(sp.sp_workspace_bytes(shape, 2) + sp.sp_vs_workspace_bytes(shape, Hq), dtype=torch.uint8, device="cuda")
+    sc = torch.empty((1, 2, nqb, nqb), dtype=torch.float32, device="cuda")
+    idx = torch.empty((1, 2, nqb, nqb), dtype=torch.int32, device="cuda")
+    cnt = torch.empty((1, 2, nqb), dtype=torch.int32, device="cuda")
+
+    def check_out(o, ref_o, what):
+        emax, emean = _err(o[0].float().cpu().numpy(), ref_o)
+        assert emax <= OUT_MAX and emean <= OUT_MEAN, f"{what}: {emax} / {emean}"
+
+    # printed construction (mean-logit scores, one selection over the map)
+    o = torch.zeros_like(q)
+    sp.sp_prefill_layer_modes(shape, q, k, v, h2c, piv, gamma, 1, 1, o, sc, idx, cnt, ws)
+    torch.cuda.synchronize()
+    idx_h, cnt_h = idx[0].cpu().numpy(), cnt[0].cpu().numpy()
+    ref = oracle.prefill_layer(*host[0], B, h2c, piv, gamma, masks=(idx_h, cnt_h), paper_pattern=True)
+    assert np.abs(sc[0].cpu().numpy() - ref["scores"]).max() <= 1e-6 + 1e-4 * ref["scores"].max()
+    for c in range(2):
+        i2, c2, _ = oracle.build_mask_global(sc[0, c].cpu().numpy(), gamma, True)
+        assert np.array_equal(i2, idx_h[c]) and np.array_equal(c2, cnt_h[c])
+    check_out(o, ref["o"], "printed construction")
+    # dictionary over two layers, open gate, then with everything sent to the vertical-slash fallback
+    for delta, fallback in ((10.0, sp.SP_FALLBACK_DENSE), (0.0, sp.SP_FALLBACK_VERTICAL_SLASH)):
+        valid = torch.zeros((1, 2), dtype=torch.int32, device="cuda")
+        a_t = torch.zeros((1, 2, nqb), dtype=torch.float32, device="cuda")
+        didx = torch.full((1, 2, nqb, nqb), -9, dtype=torch.int32, device="cuda")
+        dcnt = torch.full((1, 2, nqb), -9, dtype=torch.int32, device="cuda")
+        pd = sp.pattern_dict_of(valid, a_t, didx, dcnt)
+        vidx = torch.full((1, Hq, nqb, nqb), -3, dtype=torch.int32, device="cuda")
+        vcnt = torch.full((1, Hq, nqb), -3, dtype=torch.int32, device="cuda")
+        for l in range(2):
+            ql, kl, vl = dev[l]
+            o = torch.zeros_like(ql)
+            role = torch.full((1, Hq), -7, dtype=torch.int32, device="cuda")
+            a_hat = torch.empty((1, Hq, nqb), dtype=torch.float32, device="cuda")
+            dist = torch.empty((1, Hq, 2), dtype=torch.float32, device="cuda")
+            sp.sp_prefill_layer_dict(shape, ql, kl, vl, h2c, gamma, delta, 10.0, 0, 0, pd, o, sc, role, a_hat, dist, ws,
+                                     fallback_mode=fallback, vs_idx=vidx, vs_cnt=vcnt)
+            torch.cuda.synchronize()
+            role_h = role[0].cpu().numpy()
+            want_roles = ([-2, 0, -2, 1] if l == 0 else [0, 0, 1, 1]) if delta > 0 else [-1] * 4
+            assert list(role_h) == want_roles, (l, delta, list(role_h))
+            hq, hk, hv = host[l]
+            for h in range(Hq):
+                g = h // 2
+                if role_h[h] >= 0:
+                    c = int(role_h[h])
+                    ref_o = oracle.masked_rows(hq[:, h], hk[:, g], hv[:, g], B, didx[0, c].cpu().numpy(), dcnt[0, c].cpu().numpy())
+                elif role_h[h] == -1 and fallback == sp.SP_FALLBACK_VERTICAL_SLASH:
+                    ref_o = oracle.masked_rows(hq[:, h], hk[:, g], hv[:, g], B, vidx[0, h].cpu().numpy(), vcnt[0, h].cpu().numpy())
+                    assert np.all(vcnt[0, h].cpu().numpy() >= 1)
+                else:
+                    ref_o, _, _ = oracle.dense_rows(hq[:, h], hk[:, g], hv[:, g], B, want_scores=False)
+                emax, emean = _err(o[0, :, h].float().cpu().numpy(), ref_o)
+                assert emax <= OUT_MAX and emean <= OUT_MEAN, f"layer {l} head {h} role {role_h[h]}: {emax} / {emean}"
