@@ -153,7 +153,7 @@ struct AttnParams {
   uint16_t *o;
   int64_t q_sb, q_st, q_sh, o_sb, o_st, o_sh;
   int seq, nqb, n_kv_heads, group, n_heads, n_maps;
-  int ncol;   // slots per XCD: workgroup -> slot table below, 8 * ncol entries
+  int rgroups;  // ceil(nqb / 8): query-block rows per strand (see the workgroup mapping in attn_kernel)
   float c;    // softmax scale * log2(e)
   float *lws;     // dense: block-local log2-sum-exp [b][n][nqb][nkb][B], or null
   float *scores;  // dense: [b][n][nqb][nkb], or null
@@ -252,17 +252,31 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, c32 = lane & 31;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, kept scalar
-  // workgroup -> (XCD, column, query block, batch): workgroups are dealt round-robin to the 8 XCDs,
-  // so slot table row x lists the heads XCD x works on (heads that share a KV head sit on one XCD
-  // and meet in its L2); long rows first.
+  // workgroup -> (XCD, strand, query block, batch).  Workgroups are dealt round-robin to the 8 XCDs by the
+  // hardware.  Every listed head is cut into 8 strands (the query blocks i with (nqb-1-i) % 8 == s, all of
+  // about equal work and each spanning short and long rows); the 8n strands g = 8*slot + s, in slot-table
+  // order, are dealt to the XCDs in contiguous runs of n, so whatever n is every XCD gets the same work and
+  // works on at most ceil(n/8)+1 heads (heads that share a KV head sit next to each other and meet in its
+  // L2).  Inside an XCD the dispatch order is rows from long to short, then strand number, then head: the
+  // heads that walk the same list for the same row are neighbours in time.
   const int xcd = blockIdx.x & 7;
   int rest = blockIdx.x >> 3;
-  const int slot = xcd * p.ncol + rest % p.ncol;
-  rest /= p.ncol;
-  const int i = p.nqb - 1 - (rest % p.nqb);
-  const int b = rest / p.nqb;
+  int kk = rest % p.n_heads;  // position inside the XCD's run, enumerated strand number first, head second
+  rest /= p.n_heads;
+  const int g0 = xcd * p.n_heads, g1 = g0 + p.n_heads - 1;
+  int strand = g0;
+#pragma unroll
+  for (int sn = 0; sn < 8; ++sn) {
+    const int lo = (g0 >> 3) + (sn >= (g0 & 7) ? 0 : 1), hi = (g1 >> 3) - (sn <= (g1 & 7) ? 0 : 1);
+    const int cnt = hi - lo + 1;  // heads of the run that own a strand number sn
+    if (kk >= 0 && kk < cnt) strand = (lo + kk) * 8 + sn;
+    kk -= (cnt > 0 ? cnt : 0);
+  }
+  const int slot = strand >> 3;
+  const int i = p.nqb - 1 - ((rest % p.rgroups) * 8 + (strand & 7));
+  const int b = rest / p.rgroups;
+  if (i < 0) return;  // nqb is not a multiple of 8: this strand has one row fewer
   int head = p.head_ids[slot];
-  if (head < 0) return;  // padding slot
   const int nkb = p.nqb;
   const int hpos = p.head_pos[slot];
   if (p.head_dev) {
@@ -1648,7 +1662,7 @@ struct HeadList {
 };
 
 // Builds the slot table and launches.  The listed heads are sorted by (kv head, list, head) and
-// dealt to the 8 XCDs in contiguous runs of `ncol` slots, so heads that read the same K/V images
+// cut into 8 strands each and dealt to the 8 XCDs in contiguous runs, so heads that read the same K/V images
 // (and, for the sparse kernel, walk the same list) run on one XCD together and meet in its L2.
 template <bool DENSE>
 sp_status launch_attn(const sp_shape *s, AttnParams ap, const HeadList &hl, hipStream_t st) {
@@ -1663,13 +1677,13 @@ sp_status launch_attn(const sp_shape *s, AttnParams ap, const HeadList &hl, hipS
     return x.head < y.head;
   });
   ap.n_heads = n;
-  ap.ncol = (n + 7) / 8;
-  for (int a = 0; a < 8 * ap.ncol; ++a) {
-    ap.head_ids[a] = a < n ? ent[a].head : -1;
-    ap.head_map[a] = a < n ? ent[a].map : 0;
-    ap.head_pos[a] = a < n ? ent[a].pos : 0;
+  ap.rgroups = (ap.nqb + 7) / 8;
+  for (int a = 0; a < n; ++a) {
+    ap.head_ids[a] = ent[a].head;
+    ap.head_map[a] = ent[a].map;
+    ap.head_pos[a] = ent[a].pos;
   }
-  const int64_t nwg = (int64_t)s->batch * 8 * ap.ncol * ap.nqb;
+  const int64_t nwg = (int64_t)s->batch * 8 * n * ap.rgroups;
   if (nwg <= 0 || nwg > 0x7FFFFFFF) {
     set_err("grid too large");
     return SP_ERR_UNSUPPORTED;
