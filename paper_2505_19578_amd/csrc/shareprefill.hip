@@ -169,6 +169,9 @@ struct AttnParams {
   // optional: the query head of listed position n, chosen on the device (pivot election): [b][n_heads],
   // negative = this position is empty
   const int32_t *head_dev;
+  // optional, with head_dev: how many listed positions are occupied per batch entry ([b]) and which ones
+  // ([b][n_heads], ascending); the workgroup mapping then spreads just those over the XCDs
+  const int32_t *act_n, *act_pos;
   int32_t head_ids[SP_MAX_SLOTS];  // query head of each slot, -1 = padding slot
   int32_t head_map[SP_MAX_SLOTS];  // sparse: which list the slot's head uses
   int32_t head_pos[SP_MAX_SLOTS];  // position of the head in the caller's list (scores / lws index)
@@ -261,9 +264,14 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   // heads that walk the same list for the same row are neighbours in time.
   const int xcd = blockIdx.x & 7;
   int rest = blockIdx.x >> 3;
-  int kk = rest % p.n_heads;  // position inside the XCD's run, enumerated strand number first, head second
-  rest /= p.n_heads;
-  const int g0 = xcd * p.n_heads, g1 = g0 + p.n_heads - 1;
+  const int b = rest / (p.n_heads * p.rgroups);
+  rest %= p.n_heads * p.rgroups;
+  // number of heads this launch really has for batch entry b (all listed ones unless the device says otherwise)
+  const int n_act = p.act_n ? __builtin_amdgcn_readfirstlane(p.act_n[b]) : p.n_heads;
+  if (n_act <= 0 || rest >= n_act * p.rgroups) return;
+  int kk = rest % n_act;  // position inside the XCD's run, enumerated strand number first, head second
+  rest /= n_act;
+  const int g0 = xcd * n_act, g1 = g0 + n_act - 1;
   int strand = g0;
 #pragma unroll
   for (int sn = 0; sn < 8; ++sn) {
@@ -272,9 +280,9 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
     if (kk >= 0 && kk < cnt) strand = (lo + kk) * 8 + sn;
     kk -= (cnt > 0 ? cnt : 0);
   }
-  const int slot = strand >> 3;
-  const int i = p.nqb - 1 - ((rest % p.rgroups) * 8 + (strand & 7));
-  const int b = rest / p.rgroups;
+  int slot = strand >> 3;
+  if (p.act_pos) slot = __builtin_amdgcn_readfirstlane(p.act_pos[(int64_t)b * p.n_heads + slot]);
+  const int i = p.nqb - 1 - (rest * 8 + (strand & 7));
   if (i < 0) return;  // nqb is not a multiple of 8: this strand has one row fewer
   int head = p.head_ids[slot];
   const int nkb = p.nqb;
@@ -1007,6 +1015,8 @@ struct ElectParams {
   int32_t *role;        // [b][Hq]
   int32_t *pivot_head;  // [b][n_slots] head elected for the slot's cluster in this layer, or -1
   int32_t *route;       // [b][n_slots] dictionary map (b * n_clusters + c) the slot's lists go to, or -1
+  int32_t *act_n;       // [b] number of slots that elected a pivot
+  int32_t *act_pos;     // [b][n_slots] those slots, ascending
   int32_t *valid;       // dictionary [b][n_clusters]
   float *a_tilde;       // dictionary [b][n_clusters][nkb]
   int nkb, n_q_heads, n_slots, n_clusters;
@@ -1044,6 +1054,12 @@ __global__ __launch_bounds__(1024) void elect_kernel(ElectParams p) {
     p.route[(int64_t)b * p.n_slots + tid] = first >= 0 ? b * p.n_clusters + c : -1;
   }
   __syncthreads();
+  if (tid == 0) {
+    int na = 0;
+    for (int s2 = 0; s2 < p.n_slots; ++s2)
+      if (piv[s2] >= 0) p.act_pos[(int64_t)b * p.n_slots + na++] = s2;
+    p.act_n[b] = na;
+  }
   for (int h = w; h < p.n_q_heads; h += 16) {
     const int c = p.head_cluster[h], s = p.head_slot[h];
     int role = -1;
@@ -1671,7 +1687,7 @@ sp_status launch_attn(const sp_shape *s, AttnParams ap, const HeadList &hl, hipS
     int kvh, map, head, pos;
   } ent[SP_MAX_HEADS];
   for (int a = 0; a < n; ++a) ent[a] = {hl.head[a] / ap.group, DENSE ? 0 : hl.map[a], hl.head[a], a};
-  std::sort(ent, ent + n, [](const Ent &x, const Ent &y) {
+  std::stable_sort(ent, ent + n, [](const Ent &x, const Ent &y) {
     if (x.kvh != y.kvh) return x.kvh < y.kvh;
     if (x.map != y.map) return x.map < y.map;
     return x.head < y.head;
@@ -2031,7 +2047,7 @@ sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_
   }
   *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads) +
            std::max(pattern_layout(shape, n_dense_heads).total, pattern_layout(shape, shape->n_q_heads).total) +
-           align_up((size_t)2 * shape->batch * shape->n_q_heads * sizeof(int32_t), 256);
+           align_up((size_t)4 * shape->batch * shape->n_q_heads * sizeof(int32_t), 256);
   return SP_OK;
 }
 
@@ -2487,13 +2503,15 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
   const size_t off_lws = pack_bytes(shape);
   const size_t off_pat = off_lws + (mass ? lws_bytes(shape, n_slots) : 0);
   const size_t off_tab = off_pat + PG.total;
-  const size_t off_vs = off_tab + align_up((size_t)2 * shape->batch * Hq * sizeof(int32_t), 256);
+  const size_t off_vs = off_tab + align_up((size_t)4 * shape->batch * Hq * sizeof(int32_t), 256);
   const size_t need = off_vs + (vs ? vs_layout(shape, Hq).total : 0);
   if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   char *ws = (char *)workspace;
   int32_t *pivot_head = (int32_t *)(ws + off_tab);
   int32_t *route = pivot_head + (size_t)shape->batch * Hq;
+  int32_t *act_pos = route + (size_t)shape->batch * Hq;
+  int32_t *act_n = act_pos + (size_t)shape->batch * Hq;
 
   if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
   // 1. Alg. 3: every head's last-row estimate, then roles (election / sharing / fallback) on the device
@@ -2505,6 +2523,8 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
   ep.role = role;
   ep.pivot_head = pivot_head;
   ep.route = route;
+  ep.act_n = act_n;
+  ep.act_pos = act_pos;
   ep.valid = dict->valid;
   ep.a_tilde = dict->a_tilde;
   ep.nkb = nqb;
@@ -2527,6 +2547,8 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
     hl.n = n_slots;
     for (int s2 = 0; s2 < n_slots; ++s2) hl.head[s2] = 0;
     ap.head_dev = pivot_head;
+    ap.act_n = act_n;
+    ap.act_pos = act_pos;
     ap.n_q_heads = Hq;
     if (mass) {
       ap.lws = (float *)(ws + off_lws);
