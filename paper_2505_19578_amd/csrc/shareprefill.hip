@@ -1017,6 +1017,12 @@ struct ElectParams {
   int32_t *route;       // [b][n_slots] dictionary map (b * n_clusters + c) the slot's lists go to, or -1
   int32_t *act_n;       // [b] number of slots that elected a pivot
   int32_t *act_pos;     // [b][n_slots] those slots, ascending
+  // the heads of the role-driven attention launch, split by weight class so that each class can be spread
+  // evenly over the XCDs: positions (in that launch's slot table) of the heads that share a list, and of the
+  // heads that fall back
+  int32_t *shared_n, *shared_pos, *fallback_n, *fallback_pos;  // [b], [b][n_launch]
+  int n_launch;
+  int32_t launch_head[SP_MAX_HEADS];  // the launch's slot table: query head of each position
   int32_t *valid;       // dictionary [b][n_clusters]
   float *a_tilde;       // dictionary [b][n_clusters][nkb]
   int nkb, n_q_heads, n_slots, n_clusters;
@@ -1082,7 +1088,17 @@ __global__ __launch_bounds__(1024) void elect_kernel(ElectParams p) {
       p.dist[((int64_t)b * p.n_q_heads + h) * 2 + 1] = (float)d_sim;
     }
   }
-  __syncthreads();  // every read of the old representatives is done
+  __syncthreads();  // every read of the old representatives is done, every role is written
+  if (tid == 0) {
+    int ns = 0, nf = 0;
+    for (int pos = 0; pos < p.n_launch; ++pos) {
+      const int r = p.role[(int64_t)b * p.n_q_heads + p.launch_head[pos]];
+      if (r >= 0) p.shared_pos[(int64_t)b * p.n_launch + ns++] = pos;
+      if (r == -1) p.fallback_pos[(int64_t)b * p.n_launch + nf++] = pos;
+    }
+    p.shared_n[b] = ns;
+    p.fallback_n[b] = nf;
+  }
   for (int s = 0; s < p.n_slots; ++s) {
     if (piv[s] < 0) continue;
     const int c = p.slot_cluster[s];
@@ -1677,6 +1693,23 @@ struct HeadList {
   int32_t map[SP_MAX_HEADS];
 };
 
+// order of the slot table: heads that share a KV head, and among them those that walk the same list, adjacent
+void sort_head_list(HeadList &hl, int group, bool dense) {
+  struct Ent {
+    int kvh, map, head;
+  } ent[SP_MAX_HEADS];
+  for (int a = 0; a < hl.n; ++a) ent[a] = {hl.head[a] / group, dense ? 0 : hl.map[a], hl.head[a]};
+  std::stable_sort(ent, ent + hl.n, [](const Ent &x, const Ent &y) {
+    if (x.kvh != y.kvh) return x.kvh < y.kvh;
+    if (x.map != y.map) return x.map < y.map;
+    return x.head < y.head;
+  });
+  for (int a = 0; a < hl.n; ++a) {
+    hl.head[a] = ent[a].head;
+    hl.map[a] = ent[a].map;
+  }
+}
+
 // Builds the slot table and launches.  The listed heads are sorted by (kv head, list, head) and
 // cut into 8 strands each and dealt to the 8 XCDs in contiguous runs, so heads that read the same K/V images
 // (and, for the sparse kernel, walk the same list) run on one XCD together and meet in its L2.
@@ -2047,7 +2080,7 @@ sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_
   }
   *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads) +
            std::max(pattern_layout(shape, n_dense_heads).total, pattern_layout(shape, shape->n_q_heads).total) +
-           align_up((size_t)4 * shape->batch * shape->n_q_heads * sizeof(int32_t), 256);
+           align_up((size_t)8 * shape->batch * shape->n_q_heads * sizeof(int32_t), 256);
   return SP_OK;
 }
 
@@ -2503,7 +2536,7 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
   const size_t off_lws = pack_bytes(shape);
   const size_t off_pat = off_lws + (mass ? lws_bytes(shape, n_slots) : 0);
   const size_t off_tab = off_pat + PG.total;
-  const size_t off_vs = off_tab + align_up((size_t)4 * shape->batch * Hq * sizeof(int32_t), 256);
+  const size_t off_vs = off_tab + align_up((size_t)8 * shape->batch * Hq * sizeof(int32_t), 256);
   const size_t need = off_vs + (vs ? vs_layout(shape, Hq).total : 0);
   if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -2511,7 +2544,19 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
   int32_t *pivot_head = (int32_t *)(ws + off_tab);
   int32_t *route = pivot_head + (size_t)shape->batch * Hq;
   int32_t *act_pos = route + (size_t)shape->batch * Hq;
-  int32_t *act_n = act_pos + (size_t)shape->batch * Hq;
+  int32_t *shared_pos = act_pos + (size_t)shape->batch * Hq;
+  int32_t *fallback_pos = shared_pos + (size_t)shape->batch * Hq;
+  int32_t *act_n = fallback_pos + (size_t)shape->batch * Hq;
+  int32_t *shared_n = act_n + shape->batch, *fallback_n = shared_n + shape->batch;
+  // the role-driven launch at the end lists every clustered head (every head with the vertical-slash fallback)
+  HeadList rl;
+  for (int hq = 0; hq < Hq; ++hq)
+    if (head_to_cluster[hq] >= 0 || vs) {
+      rl.head[rl.n] = hq;
+      rl.map[rl.n] = head_to_cluster[hq] >= 0 ? head_to_cluster[hq] : dict->n_clusters + hq;
+      ++rl.n;
+    }
+  sort_head_list(rl, shape->n_q_heads / shape->n_kv_heads, false);
 
   if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
   // 1. Alg. 3: every head's last-row estimate, then roles (election / sharing / fallback) on the device
@@ -2525,6 +2570,12 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
   ep.route = route;
   ep.act_n = act_n;
   ep.act_pos = act_pos;
+  ep.shared_n = shared_n;
+  ep.shared_pos = shared_pos;
+  ep.fallback_n = fallback_n;
+  ep.fallback_pos = fallback_pos;
+  ep.n_launch = rl.n;
+  for (int a = 0; a < rl.n; ++a) ep.launch_head[a] = rl.head[a];
   ep.valid = dict->valid;
   ep.a_tilde = dict->a_tilde;
   ep.nkb = nqb;
@@ -2582,26 +2633,24 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
     }
   }
   // 5. heads by role: shared -> the dictionary's lists, fallback -> dense or their vertical-slash lists,
-  //    pivot -> done above
-  fill_attn(ap, shape, q, workspace, o);
-  hl.n = 0;
-  for (int hq = 0; hq < Hq; ++hq)
-    if (head_to_cluster[hq] >= 0 || vs) {
-      hl.head[hl.n] = hq;
-      hl.map[hl.n] = head_to_cluster[hq] >= 0 ? head_to_cluster[hq] : dict->n_clusters + hq;
-      ++hl.n;
+  //    pivot -> done above.  Two launches over the same slot table, each restricted on the device to one
+  //    weight class (a list-walking head costs a fraction of a falling-back one) and spread over all XCDs.
+  if (rl.n) {
+    for (int cls = 0; cls < 2; ++cls) {
+      fill_attn(ap, shape, q, workspace, o);
+      ap.n_maps = dict->n_clusters;
+      ap.kb_idx = dict->kb_idx;
+      ap.kb_cnt = dict->kb_cnt;
+      ap.head_pattern = role;
+      ap.n_q_heads = Hq;
+      ap.act_n = cls == 0 ? shared_n : fallback_n;
+      ap.act_pos = cls == 0 ? shared_pos : fallback_pos;
+      if (vs) {
+        ap.priv_idx = vs_idx;
+        ap.priv_cnt = vs_cnt;
+      }
+      if ((rc = launch_attn<false>(shape, ap, rl, st))) return rc;
     }
-  if (hl.n) {
-    ap.n_maps = dict->n_clusters;
-    ap.kb_idx = dict->kb_idx;
-    ap.kb_cnt = dict->kb_cnt;
-    ap.head_pattern = role;
-    ap.n_q_heads = Hq;
-    if (vs) {
-      ap.priv_idx = vs_idx;
-      ap.priv_cnt = vs_cnt;
-    }
-    if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
   }
   return SP_OK;
 }
