@@ -1109,6 +1109,27 @@ __global__ __launch_bounds__(1024) void elect_kernel(ElectParams p) {
   }
 }
 
+// Splits the heads of a role-driven attention launch into the two weight classes (sharing a list / falling
+// back) so that each class can be spread evenly over the XCDs; positions refer to the launch's slot table.
+struct ClassifyParams {
+  const int32_t *role;  // [b][n_q_heads]
+  int32_t *shared_n, *shared_pos, *fallback_n, *fallback_pos;  // [b], [b][n_launch]
+  int n_q_heads, n_launch;
+  int32_t launch_head[SP_MAX_HEADS];
+};
+__global__ __launch_bounds__(64) void classify_heads_kernel(ClassifyParams p) {
+  const int b = blockIdx.x;
+  if (threadIdx.x != 0) return;
+  int ns = 0, nf = 0;
+  for (int pos = 0; pos < p.n_launch; ++pos) {
+    const int r = p.role[(int64_t)b * p.n_q_heads + p.launch_head[pos]];
+    if (r >= 0) p.shared_pos[(int64_t)b * p.n_launch + ns++] = pos;
+    if (r == -1) p.fallback_pos[(int64_t)b * p.n_launch + nf++] = pos;
+  }
+  p.shared_n[b] = ns;
+  p.fallback_n[b] = nf;
+}
+
 // ---- Alg. 2 over the flattened map, exact integers -------------------------------------------
 // With u = the 24-bit score, T = ceil(gamma_q * total / 2^24): the kept set is every entry above
 // a threshold value v* plus the first `need` entries equal to v* in flat (row-major) order, where v*
@@ -2376,7 +2397,8 @@ static sp_status prefill_impl(const sp_shape *shape, const void *q, const void *
   const size_t off_pat = off_lws + (mass ? lws_bytes(shape, n_clusters) : 0);
   const PatternLayout PL = pattern_layout(shape, n_clusters);
   const PatternLayout PG = pattern_layout(shape, Hq);  // the gate pools every head
-  const size_t need = off_pat + (pattern_ws ? (gated ? PG.total : PL.total) : 0);
+  const size_t off_tab = off_pat + (pattern_ws ? (gated ? PG.total : PL.total) : 0);
+  const size_t need = off_tab + (gated ? align_up((size_t)8 * shape->batch * Hq * sizeof(int32_t), 256) : 0);
   if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   const int nqb = shape->seq / shape->block;
@@ -2433,13 +2455,40 @@ static sp_status prefill_impl(const sp_shape *shape, const void *q, const void *
       hl.map[hl.n] = head_to_cluster[hq];
       ++hl.n;
     }
-  if (hl.n) {
+  if (hl.n && !gated) {
     ap.n_maps = n_clusters;
     ap.kb_idx = kb_idx;
     ap.kb_cnt = kb_cnt;
-    ap.head_pattern = gated ? head_pattern : nullptr;
     ap.n_q_heads = Hq;
     if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
+  }
+  if (hl.n && gated) {
+    // the gate's verdicts live on the device: split the heads there into those that share a list and those
+    // that fall back to dense, and launch each class on its own, spread evenly over the XCDs
+    sort_head_list(hl, Hq / shape->n_kv_heads, false);
+    ClassifyParams cp;
+    memset(&cp, 0, sizeof(cp));
+    cp.role = head_pattern;
+    cp.shared_pos = (int32_t *)(ws + off_tab);
+    cp.fallback_pos = cp.shared_pos + (size_t)shape->batch * Hq;
+    cp.shared_n = cp.fallback_pos + (size_t)shape->batch * Hq;
+    cp.fallback_n = cp.shared_n + shape->batch;
+    cp.n_q_heads = Hq;
+    cp.n_launch = hl.n;
+    for (int a = 0; a < hl.n; ++a) cp.launch_head[a] = hl.head[a];
+    hipLaunchKernelGGL(classify_heads_kernel, dim3(shape->batch), dim3(64), 0, st, cp);
+    if ((rc = hip_check(hipGetLastError(), "classify_heads_kernel launch"))) return rc;
+    for (int cls = 0; cls < 2; ++cls) {
+      fill_attn(ap, shape, q, workspace, o);
+      ap.n_maps = n_clusters;
+      ap.kb_idx = kb_idx;
+      ap.kb_cnt = kb_cnt;
+      ap.head_pattern = head_pattern;
+      ap.n_q_heads = Hq;
+      ap.act_n = cls == 0 ? cp.shared_n : cp.fallback_n;
+      ap.act_pos = cls == 0 ? cp.shared_pos : cp.fallback_pos;
+      if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
+    }
   }
   return SP_OK;
 }
