@@ -1074,8 +1074,9 @@ __global__ __launch_bounds__(1024) void elect_kernel(ElectParams p) {
       if (piv[s] == h) {
         role = -2;
       } else {
+        // heads met before the pivot of a new entry saw an empty dictionary: no representative for them
         const float *ref = had[s] ? p.a_tilde + ((int64_t)b * p.n_clusters + c) * p.nkb
-                                  : (piv[s] >= 0 ? ah + (int64_t)piv[s] * p.nkb : nullptr);
+                                  : (piv[s] >= 0 && piv[s] < h ? ah + (int64_t)piv[s] * p.nkb : nullptr);
         if (ref) {
           d_sim = js_distance_wave(ah + (int64_t)h * p.nkb, ref, p.nkb, lane);
           if (ds[h] < (double)p.delta && d_sim < (double)p.tau) role = c;

@@ -221,3 +221,18 @@ def test_dict_batch_of_two_prompts_equals_two_single_runs():
         print(f"[dict batch 2] fallback {fallback}: layer-0 roles {roles.tolist()}", flush=True)
         if fallback == sp.SP_FALLBACK_VERTICAL_SLASH:
             assert (roles == -1).any()
+
+
+def test_dict_permuted_clusters_with_fallbacks():
+    """Clusters that straddle KV heads (a seeded permutation of the heads): the slot table of the role-driven
+    launches is then not in head order, which the device-side compaction of sharing / falling-back heads has to
+    follow.  Open gates, then a sparsity threshold that sends part of the heads to the dense fallback."""
+    g = _run_and_check("qwen7b_128k", 4096, 2, 10.0, 10.0, label="qwen7b@4k open")
+    assert sum(1 for r in g[0]["role"] if r == -2) == 7 and all(r >= 0 for r in g[1]["role"])
+    ds = np.sort(np.concatenate([x["dist"][:, 0] for x in g]))
+    lo, hi = len(ds) // 4, 3 * len(ds) // 4
+    i = lo + int(np.argmax(ds[lo + 1:hi + 1] - ds[lo:hi]))
+    assert ds[i + 1] - ds[i] > 4e-4
+    g = _run_and_check("qwen7b_128k", 4096, 2, float(0.5 * (ds[i] + ds[i + 1])), 10.0, label="qwen7b@4k sparsity gate")
+    roles = np.array([x["role"] for x in g])
+    assert (roles == -1).any() and (roles >= 0).any()
