@@ -322,8 +322,9 @@ typedef struct {
  *                   in head_to_cluster (ascending cluster id); slot s is written only if its
  *                   cluster elected a pivot in this call
  *   role            device int32 [batch][n_q_heads]      (output)
- *   a_hat, dist     device fp32 [batch][n_q_heads][nkb] / [batch][n_q_heads][2]   (outputs, Alg. 3; heads
- *                   without a cluster get their estimate and d_sparse too, with d_sim = 0)
+ *   a_hat, dist     device fp32 [batch][n_q_heads][nkb] / [batch][n_q_heads][2]   (outputs, Alg. 3; d_sim is 0
+ *                   where no representative existed when the head was met: pivots, heads before their
+ *                   cluster's new pivot, heads without a cluster -- these still get a_hat and d_sparse)
  *   vs_idx, vs_cnt  device int32 [batch][n_q_heads][nqb][nkb] / [batch][n_q_heads][nqb]: the lists of
  *                   the heads that took the vertical-slash fallback (other heads' entries are left
  *                   untouched); may be NULL with SP_FALLBACK_DENSE

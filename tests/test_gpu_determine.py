@@ -169,7 +169,7 @@ def _check_gated_layer(sp, cfg, L, dev, host, rows, delta, tau, label, h2c=None,
     return pat_h, dist.cpu().numpy()[0]
 
 
-@pytest.mark.parametrize("name,seq", [("tiny", None), ("llama8b_32k", 2048)])
+@pytest.mark.parametrize("name,seq", [("tiny", None), ("llama8b_32k", 2048), ("qwen7b_128k", 4096)])
 def test_gated_layer_small(name, seq):
     sp, cfg, L, dev, host = _setup(name, seq=seq)
     rows = np.arange(cfg.seq // cfg.block)
