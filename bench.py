@@ -148,6 +148,8 @@ def main() -> int:
                          "(sp_prefill_layer_dict; thresholds from --gate, default 10,0.2) and print that line instead")
     ap.add_argument("--fallback", choices=["dense", "vs"], default="dense",
                     help="with --dict-layers: what heads that fail Alg. 3 run (dense, or the vertical-slash pattern of Alg. 5)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step into a HIP graph and time replays (the calls enqueue kernels only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-all", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -203,6 +205,19 @@ def main() -> int:
         else:
             sp.sp_prefill_layer_modes(shape, q, k, v, h2c, piv, cfg.gamma, score_mode, select_mode, o, scores,
                                       kb_idx, kb_cnt, ws)
+
+    if args.graph:
+        eager_step = step
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            eager_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager_step()
+        step = graph.replay
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
@@ -284,6 +299,7 @@ def main() -> int:
                    "seed": L["seed"], "density": density},
         "ms_per_layer": ms_step,
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "hip_graph": bool(args.graph),
         "pattern": {"score_mode": args.score_mode, "select_mode": args.select_mode,
                     "gate": None if not gate else {"delta": gate[0], "tau": gate[1], "heads_fallen_back": len(fell_back)}},
         "computed_tflops": computed_flops / (ms_step * 1e-3) / 1e12,
