@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM/fabric bytes per launch of the dense-pivot kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # passes summarised in profiles/prefill_layer_llama8b_128k.md (counters scaled by a 1 GiB copy; a
 # benchmark run cannot collect counters itself, so the figure is carried here per workload)
-MEASURED_TRAFFIC_BYTES = {"llama8b_128k": 14.25e9}
+MEASURED_TRAFFIC_BYTES = {"llama8b_128k": 14.01e9}
 
 
 def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
