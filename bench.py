@@ -129,6 +129,40 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
     return 0
 
 
+def bench_mix_probe(args, sp, torch) -> int:
+    """What the machine sustains for the instruction mix of one attention step, on operand data like the
+    workload's (standard-normal bf16) and on zeros: the matrix-pipe clock of the part depends on the data."""
+    n16 = sp.SP_PROBE_OPERAND_BYTES // 2
+    g = torch.Generator(device="cuda")
+    g.manual_seed(20250519)
+    data = {"normal": torch.randn(n16, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16),
+            "zeros": torch.zeros(n16, device="cuda", dtype=torch.bfloat16)}
+    sink = torch.empty(sp.SP_PROBE_SINK_BYTES // 4, dtype=torch.float32, device="cuda")
+    iters, out = 40000, {}
+    for kind, operands in data.items():
+        for mix, name in enumerate(sp.SP_PROBE_MIXES):
+            n_it = iters // (2 if name == "step_64q" else 1)      # 64 MFMAs per step instead of 32
+            for _ in range(max(args.warmup, 1)):
+                flops = sp.sp_probe_step_mix(mix, operands, n_it, sink)
+            marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+            marks[0].record()
+            for n in range(args.steps):
+                sp.sp_probe_step_mix(mix, operands, n_it, sink)
+                marks[n + 1].record()
+            torch.cuda.synchronize()
+            ms = sorted(marks[n].elapsed_time(marks[n + 1]) for n in range(args.steps))
+            tf = flops / (ms[len(ms) // 2] * 1e-3) / 1e12
+            out[f"{kind}/{name}"] = {"ms_median": round(ms[len(ms) // 2], 3), "tflops": round(tf, 1),
+                                     "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+            print(f"mix-probe {kind:7s} {name:9s} {ms[len(ms) // 2]:8.2f} ms  {tf:7.1f} TFLOP/s  "
+                  f"{tf / PEAK_BF16_TFLOPS:.3f} of peak", file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "step-mix probe: matrix TFLOP/s sustained by the instruction mix of one attention step",
+                      "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
+                      "peak": PEAK_BF16_TFLOPS, "data": "synthetic (standard-normal bf16 operands, and zeros)",
+                      "mixes": out}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,6 +184,9 @@ def main() -> int:
                     help="with --dict-layers: what heads that fail Alg. 3 run (dense, or the vertical-slash pattern of Alg. 5)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into a HIP graph and time replays (the calls enqueue kernels only)")
+    ap.add_argument("--mix-probe", action="store_true",
+                    help="instead of the layer: time the library's step-mix probe (the instruction mix of one "
+                         "attention step on normal and on zero operand data), one JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-all", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -166,6 +203,8 @@ def main() -> int:
     from synth import CONFIGS, make_layer
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.mix_probe:
+        return bench_mix_probe(args, sp, torch)
     if args.dict_layers > 0:
         return bench_dict(args, sp, torch, np, CONFIGS, make_layer)
     t0 = time.time()

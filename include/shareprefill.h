@@ -338,6 +338,40 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
                                 float *dist, int32_t *vs_idx, int32_t *vs_cnt, void *workspace, size_t workspace_bytes,
                                 void *hip_stream);
 
+/*
+ * Measurement aid, not a step of the method: the instruction mix of one attention step of the
+ * kernels above with nothing around it, so that the rate the attention kernels reach can be read
+ * against what this machine sustains for the same mix on the same kind of operand data (the
+ * matrix-pipe rate of the part depends on the operand values: it lowers its clock under the
+ * switching power of random data).  Every wavefront of a grid that fills the device runs
+ * `iters` steps; a step is 32 (mix 4: 64) v_mfma_f32_32x32x16_bf16 plus, depending on `mix`,
+ *   SP_PROBE_MFMA      nothing else
+ *   SP_PROBE_LDS_READ  + one 1 KiB LDS fragment read per MFMA (the streamed K / V operand)
+ *   SP_PROBE_RING      + 8 LDS-direct 1 KiB loads per wavefront and step and one barrier per step
+ *   SP_PROBE_STEP      + 4 fp32 FMAs and one exp2 per MFMA (the softmax's share): this library's step
+ *   SP_PROBE_STEP_64Q  the same work per MFMA for 64 queries per wavefront: a fragment read every
+ *                      second MFMA, half the LDS-direct loads per MFMA, one wavefront per SIMD
+ *   operands    device, bf16 values the matrix pipe is fed with, at least SP_PROBE_OPERAND_BYTES,
+ *               16-byte aligned; read only
+ *   iters       1 .. 1000000
+ *   sink        device fp32, at least SP_PROBE_SINK_BYTES; receives one value per lane (ignored data)
+ *   mfma_flops  host, output: matrix flops of the launch (2*32*32*16 per MFMA and wavefront)
+ * The call only enqueues the kernel on hip_stream; the caller times it (HIP events on that stream).
+ * Returns SP_ERR_INVALID_ARG for a null pointer, a misaligned or short buffer, an unknown mix or
+ * iters out of range.
+ */
+enum {
+  SP_PROBE_MFMA = 0,
+  SP_PROBE_LDS_READ = 1,
+  SP_PROBE_RING = 2,
+  SP_PROBE_STEP = 3,
+  SP_PROBE_STEP_64Q = 4
+};
+#define SP_PROBE_OPERAND_BYTES ((size_t)64 << 20)
+#define SP_PROBE_SINK_BYTES ((size_t)4 << 20)
+sp_status sp_probe_step_mix(int32_t mix, const void *operands, size_t operand_bytes, int32_t iters, float *sink,
+                            size_t sink_bytes, double *mfma_flops, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

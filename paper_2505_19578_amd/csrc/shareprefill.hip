@@ -2036,6 +2036,91 @@ sp_status check_ws(const void *ws, size_t have, size_t need) {
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------------
+// step-mix probe (measurement aid): the instruction mix of one attention step, nothing around it
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+// Per step and wavefront: G MFMAs on four independent accumulators; a 1 KiB fragment read from LDS for
+// every LP-th MFMA (4 groups ahead of its use, as in attn_kernel); C LDS-direct 1 KiB loads spread over
+// the groups; V FMAs and E exp2 per MFMA; a barrier per step when there are loads.  LDS: a 32 KiB read
+// window, above it the wavefronts' load windows.  Every workgroup streams its own 1 MiB of `src`.
+template <int LP, int C, int V, int E, int G, int LDSB>
+__global__ __launch_bounds__(256) void probe_kernel(const char *__restrict__ src, float *__restrict__ sink, int iters) {
+  static_assert(32768 + 4 * C * 1024 <= LDSB, "load windows must fit");
+  static_assert(G <= 64 && (C == 0 || G % C == 0), "group layout");
+  __shared__ __attribute__((aligned(1024))) char smem[LDSB];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const char *gsrc = src + (size_t)(blockIdx.x % 64) * (1 << 20);
+  for (int i = tid; i < 32768 / 16; i += 256)
+    reinterpret_cast<u32x4 *>(smem)[i] = reinterpret_cast<const u32x4 *>(gsrc)[i];
+  __syncthreads();
+  const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
+  const bf16x8 b = reinterpret_cast<const bf16x8 *>(gsrc + 65536)[tid];
+  f32x16 acc[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
+  float x[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) x[i] = 0.5f + 0.01f * i + lane * 1e-4f;
+  const char *rd = smem + lane * 16;
+  constexpr int PF = 4;
+  bf16x8 fr[PF + 1];
+#pragma unroll
+  for (int n = 0; n < PF + 1; ++n) fr[n] = b;
+  for (int it = 0; it < iters; ++it) {
+    if (C > 0) {
+      wait_vm<C / 2>();
+      __builtin_amdgcn_s_barrier();
+    }
+    const char *gs = gsrc + (size_t)(it & 7) * 65536 + (size_t)(w * C) * 1024 + 131072;
+    const uint32_t wslot = lds0 + 32768 + (uint32_t)(w * C) * 1024;
+#pragma unroll
+    for (int n = 0; n < G; ++n) {
+      if (LP > 0 && n % LP == 0)
+        fr[(n + PF) % (PF + 1)] = *reinterpret_cast<const bf16x8 *>(rd + (n % 32) * 1024);
+      acc[n % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[LP > 0 ? ((n / LP) * LP) % (PF + 1) : 0], b, acc[n % 4],
+                                                           0, 0, 0);
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const int i = (n * V + v) % 16;
+        x[i] = __builtin_fmaf(x[i], 0.999f, 0.0007f);
+      }
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const float y = fast_exp2(x[(n * E + e + 8) % 16]);
+        asm volatile("" ::"v"(y));
+      }
+      if (C > 0 && n % (G / (C > 0 ? C : 1)) == 1) {
+        constexpr int GAP = G / (C > 0 ? C : 1);
+        lds_dma16(gs + (n / GAP) * 1024, lane * 16, wslot + (n / GAP) * 1024);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  wait_vm<0>();
+  float s = 0.f;
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[n][r];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += x[i];
+  sink[(size_t)blockIdx.x * 256 + tid] = s;
+}
+
+template <int LP, int C, int V, int E, int G, int LDSB>
+sp_status launch_probe(const void *operands, float *sink, int iters, int n_wg, hipStream_t st) {
+  hipLaunchKernelGGL((probe_kernel<LP, C, V, E, G, LDSB>), dim3(n_wg), dim3(256), 0, st, (const char *)operands, sink,
+                     iters);
+  return hip_check(hipGetLastError(), "probe_kernel launch");
+}
+
+}  // namespace
+
 extern "C" {
 
 const char *sp_status_string(sp_status s) {
@@ -2749,6 +2834,47 @@ sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, 
   return sp_prefill_layer_modes(shape, q, k, v, head_to_cluster, pivot_heads, n_clusters, gamma, SP_SCORE_BLOCK_MASS,
                                 SP_SELECT_PER_ROW, o, block_scores, kb_idx, kb_cnt, workspace, workspace_bytes,
                                 hip_stream);
+}
+
+sp_status sp_probe_step_mix(int32_t mix, const void *operands, size_t operand_bytes, int32_t iters, float *sink,
+                            size_t sink_bytes, double *mfma_flops, void *hip_stream) {
+  g_err[0] = 0;
+  if (!operands || !sink || !mfma_flops) {
+    set_err("operands / sink / mfma_flops must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (((uintptr_t)operands & 15) || operand_bytes < SP_PROBE_OPERAND_BYTES || sink_bytes < SP_PROBE_SINK_BYTES) {
+    set_err("operands must be 16-byte aligned and hold %zu bytes, sink %zu bytes", (size_t)SP_PROBE_OPERAND_BYTES,
+            (size_t)SP_PROBE_SINK_BYTES);
+    return SP_ERR_INVALID_ARG;
+  }
+  if (mix < SP_PROBE_MFMA || mix > SP_PROBE_STEP_64Q || iters < 1 || iters > 1000000) {
+    set_err("mix %d outside [0, 4] or iters %d outside [1, 1000000]", mix, iters);
+    return SP_ERR_INVALID_ARG;
+  }
+  int dev = 0, cus = 0;
+  sp_status rc;
+  if ((rc = hip_check(hipGetDevice(&dev), "hipGetDevice"))) return rc;
+  if ((rc = hip_check(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev),
+                      "hipDeviceGetAttribute")))
+    return rc;
+  // two workgroups of four wavefronts per CU (80 KiB of LDS each), one for the 64-query mix (160 KiB)
+  const int wg_per_cu = mix == SP_PROBE_STEP_64Q ? 1 : 2;
+  const int n_wg = cus * wg_per_cu;
+  if (cus < 1 || (size_t)n_wg * 256 * sizeof(float) > SP_PROBE_SINK_BYTES) {
+    set_err("device reports %d compute units", cus);
+    return SP_ERR_UNSUPPORTED;
+  }
+  const int g = mix == SP_PROBE_STEP_64Q ? 64 : 32;
+  *mfma_flops = (double)n_wg * 4 * (double)iters * g * (2.0 * 32 * 32 * 16);
+  hipStream_t st = (hipStream_t)hip_stream;
+  switch (mix) {
+    case SP_PROBE_MFMA: return launch_probe<0, 0, 0, 0, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
+    case SP_PROBE_LDS_READ: return launch_probe<1, 0, 0, 0, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
+    case SP_PROBE_RING: return launch_probe<1, 8, 0, 0, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
+    case SP_PROBE_STEP: return launch_probe<1, 8, 4, 1, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
+    default: return launch_probe<2, 4, 4, 1, 64, 160 * 1024>(operands, sink, iters, n_wg, st);
+  }
 }
 
 }  // extern "C"
