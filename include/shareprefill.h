@@ -349,8 +349,8 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
  *   SP_PROBE_LDS_READ  + one 1 KiB LDS fragment read per MFMA (the streamed K / V operand)
  *   SP_PROBE_RING      + 8 LDS-direct 1 KiB loads per wavefront and step and one barrier per step
  *   SP_PROBE_STEP      + 4 fp32 FMAs and one exp2 per MFMA (the softmax's share): this library's step
- *   SP_PROBE_STEP_64Q  the same work per MFMA for 64 queries per wavefront: a fragment read every
- *                      second MFMA, half the LDS-direct loads per MFMA, one wavefront per SIMD
+ *   SP_PROBE_STEP_64Q  the same work per MFMA for 64 queries per wavefront: 64 MFMAs per step, a fragment
+ *                      read every second MFMA, the same 8 LDS-direct loads per step, one wavefront per SIMD
  *   operands    device, bf16 values the matrix pipe is fed with, at least SP_PROBE_OPERAND_BYTES,
  *               16-byte aligned; read only
  *   iters       1 .. 1000000

@@ -2873,7 +2873,7 @@ sp_status sp_probe_step_mix(int32_t mix, const void *operands, size_t operand_by
     case SP_PROBE_LDS_READ: return launch_probe<1, 0, 0, 0, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
     case SP_PROBE_RING: return launch_probe<1, 8, 0, 0, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
     case SP_PROBE_STEP: return launch_probe<1, 8, 4, 1, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
-    default: return launch_probe<2, 4, 4, 1, 64, 160 * 1024>(operands, sink, iters, n_wg, st);
+    default: return launch_probe<2, 8, 4, 1, 64, 160 * 1024>(operands, sink, iters, n_wg, st);
   }
 }
 
