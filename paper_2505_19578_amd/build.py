@@ -16,7 +16,7 @@ HIPCC_FLAGS = [
     # device code never relies on NaN semantics (the score quantiser tests bits); lets fmax chains
     # compile to v_max3 without a canonicalising v_max per operand
     "-Xarch_device", "-fno-honor-nans",
-    "-I" + os.path.join(ROOT, "include"),
+    "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc"),
 ]
 
 

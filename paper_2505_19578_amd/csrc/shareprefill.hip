@@ -1,5 +1,8 @@
 // SharePrefill prefill attention for one layer on gfx950 (MI355X): HIP kernels + C ABI.
 //
+// This file is the host side (argument checks, workspace layouts, launchers, the C ABI) and the only
+// translation unit; the kernels live in the headers it includes.
+//
 // Kernels
 //   pack_kv_kernel   K/V [token][kv head][d] -> per (kv head, 64-key sub-tile) images laid out
 //                    in MFMA-operand order, so the attention kernels move a sub-tile from HBM
@@ -36,1513 +39,16 @@
 
 #include "shareprefill.h"
 
+#include "sp_common.h"
+#include "pack_kernel.h"
+#include "attn_kernel.h"
+#include "mask_kernel.h"
+#include "pattern_kernels.h"
+#include "global_select_kernels.h"
+#include "vertical_slash_kernels.h"
+#include "probe_kernel.h"
+
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-constexpr int SP_MAX_HEADS = 128;
-constexpr int KT = 64;  // keys per sub-tile
-
-thread_local char g_err[512] = "";
-
-// Optional per-kernel timing (sp_profile_enable / sp_profile_read): every launch is bracketed
-// by two HIP events on the caller's stream.  Process-wide, not thread-safe; meant for benches.
-enum KernelKind { KK_PACK = 0, KK_DENSE = 1, KK_MASK = 2, KK_SPARSE = 3, KK_SCORE = 4, KK_VS = 5, KK_COUNT = 6 };
-struct ProfRec {
-  int kind;
-  hipEvent_t e0, e1;
-};
-bool g_prof_on = false;
-std::vector<ProfRec> g_prof;
-
-struct ProfScope {
-  hipStream_t st;
-  bool on;
-  ProfRec rec;
-  ProfScope(int kind, hipStream_t s) : st(s), on(g_prof_on) {
-    if (!on) return;
-    rec.kind = kind;
-    if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) {
-      on = false;
-      return;
-    }
-    (void)hipEventRecord(rec.e0, st);
-  }
-  ~ProfScope() {
-    if (!on) return;
-    (void)hipEventRecord(rec.e1, st);
-    g_prof.push_back(rec);
-  }
-};
-
-void set_err(const char *fmt, ...) {
-  va_list ap;
-  va_start(ap, fmt);
-  vsnprintf(g_err, sizeof(g_err), fmt, ap);
-  va_end(ap);
-}
-
-// ---------------------------------------------------------------------------------------------
-// pack kernel
-// ---------------------------------------------------------------------------------------------
-struct PackParams {
-  const uint16_t *k, *v;
-  char *out;
-  int64_t sb, st, sh;  // kv strides (elements)
-  int n_kv_heads, n_sub;  // n_sub = seq / 64
-};
-
-// One workgroup packs one (batch, kv head, 64-key sub-tile): K image then V image.
-template <int D>
-__global__ __launch_bounds__(256) void pack_kv_kernel(PackParams p) {
-  constexpr int IMG = KT * D * 2;       // bytes of one packed K (or V) image
-  constexpr int NCH = IMG / 16;         // 16-byte chunks per image
-  constexpr int DS = D / 16;
-  constexpr int VROW = D + 8;           // padded LDS row (elements)
-  __shared__ __attribute__((aligned(16))) uint16_t vs[KT * VROW];
-  const int kt = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x;
-  const int64_t base = (int64_t)b * p.sb + (int64_t)kt * KT * p.st + (int64_t)kvh * p.sh;
-  char *out = p.out + (((int64_t)b * p.n_kv_heads + kvh) * p.n_sub + kt) * (int64_t)(2 * IMG);
-
-  // stage V rows into LDS (row-major, padded)
-  for (int c = tid; c < KT * (D / 8); c += 256) {
-    const int key = c / (D / 8), part = c % (D / 8);
-    const u32x4 val = *reinterpret_cast<const u32x4 *>(p.v + base + (int64_t)key * p.st + part * 8);
-    *reinterpret_cast<u32x4 *>(&vs[key * VROW + part * 8]) = val;
-  }
-  // K image: fragment f = rb*DS + ds, lane holds key 32rb + c, d = 16ds + 8h ..+7
-  for (int c = tid; c < NCH; c += 256) {
-    const int f = c >> 6, lane = c & 63;
-    const int rb = f / DS, ds = f % DS;
-    const int key = 32 * rb + (lane & 31), dpos = 16 * ds + 8 * (lane >> 5);
-    const u32x4 val = *reinterpret_cast<const u32x4 *>(p.k + base + (int64_t)key * p.st + dpos);
-    *reinterpret_cast<u32x4 *>(out + (int64_t)c * 16) = val;
-  }
-  __syncthreads();
-  // V image: fragment f = db*4 + ks, lane holds dd = 32db + c, keys 16ks + slot(h, e)
-  for (int c = tid; c < NCH; c += 256) {
-    const int f = c >> 6, lane = c & 63;
-    const int db = f >> 2, ks = f & 3;
-    const int dd = 32 * db + (lane & 31), h = lane >> 5;
-    uint32_t w[4];
-#pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {
-      const int e = 2 * e2;
-      const int key0 = 16 * ks + ((e < 4) ? (4 * h + e) : (8 + 4 * h + (e - 4)));
-      const uint32_t lo = vs[key0 * VROW + dd], hi = vs[(key0 + 1) * VROW + dd];
-      w[e2] = lo | (hi << 16);
-    }
-    u32x4 val = {w[0], w[1], w[2], w[3]};
-    *reinterpret_cast<u32x4 *>(out + IMG + (int64_t)c * 16) = val;
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// attention kernel
-// ---------------------------------------------------------------------------------------------
-constexpr int SP_MAX_SLOTS = SP_MAX_HEADS + 8;
-struct AttnParams {
-  const uint16_t *q;
-  const char *kvp;  // packed K/V images
-  uint16_t *o;
-  int64_t q_sb, q_st, q_sh, o_sb, o_st, o_sh;
-  int seq, nqb, n_kv_heads, group, n_heads, n_maps;
-  int rgroups;  // ceil(nqb / 8): query-block rows per strand (see the workgroup mapping in attn_kernel)
-  float c;    // softmax scale * log2(e)
-  float *lws;     // dense: block-local log2-sum-exp [b][n][nqb][nkb][B], or null
-  float *scores;  // dense: [b][n][nqb][nkb], or null
-  const int32_t *kb_idx;  // sparse: [b][n_maps][nqb][nkb]
-  const int32_t *kb_cnt;  // sparse: [b][n_maps][nqb]
-  // sparse, optional: per (batch entry, query head) pattern chosen on the device (Alg. 3's gate):
-  // a list index in [0, n_maps), or < 0 = no shared pattern, the head walks every key block 0..i
-  const int32_t *head_pattern;  // [b][n_q_heads]; <= -2 = nothing to do for this head in this launch
-  int n_q_heads;
-  // optional: private lists per (batch entry, query head), used by a head whose head_pattern entry is -1
-  // (its vertical-slash pattern) instead of the dense walk: [b][n_q_heads][nqb][nkb] / [b][n_q_heads][nqb]
-  const int32_t *priv_idx, *priv_cnt;
-  // optional: the query head of listed position n, chosen on the device (pivot election): [b][n_heads],
-  // negative = this position is empty
-  const int32_t *head_dev;
-  // optional, with head_dev: how many listed positions are occupied per batch entry ([b]) and which ones
-  // ([b][n_heads], ascending); the workgroup mapping then spreads just those over the XCDs
-  const int32_t *act_n, *act_pos;
-  int32_t head_ids[SP_MAX_SLOTS];  // query head of each slot, -1 = padding slot
-  int32_t head_map[SP_MAX_SLOTS];  // sparse: which list the slot's head uses
-  int32_t head_pos[SP_MAX_SLOTS];  // position of the head in the caller's list (scores / lws index)
-};
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
-
-// max / sum of a value with its partner in lane ^ 32 (one v_permlane32_swap, no LDS round trip)
-__device__ __forceinline__ float max_xor32(float x) {
-  const uint32_t u = __builtin_bit_cast(uint32_t, x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
-}
-__device__ __forceinline__ float sum_xor32(float x) {
-  const uint32_t u = __builtin_bit_cast(uint32_t, x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
-}
-
-// Reference point of the online softmax.  The running reference m only has to stay within
-// SP_MAX_SLACK (log2 units) of the true running max: P = 2^(x - m) is then at most 2^SP_MAX_SLACK,
-// harmless in fp32 / bf16, and m, l, the block sums and O stay mutually consistent whatever m is.
-// Moving m only when the max outgrows it by more than the slack makes O rescaling rare (a lane
-// triggers it a handful of times per row instead of at every new maximum).
-constexpr float SP_MAX_SLACK = 8.0f;
-__device__ __forceinline__ float lazy_max(float m_ref, float tile_max) {
-  return (tile_max > m_ref + SP_MAX_SLACK) ? tile_max : m_ref;
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  f32x2 t = {a, b};
-  bf16x2 r = __builtin_convertvector(t, bf16x2);
-  return __builtin_bit_cast(uint32_t, r);
-}
-
-// One wavefront-wide 1 KiB copy HBM/L2 -> LDS without passing through registers: lane l moves the
-// 16 bytes at g_uniform + lane_off to LDS byte address lds_base + 16 l (g_uniform and lds_base are
-// wave-uniform).  Issued from inline assembly so that the compiler does not serialise it against
-// the kernel's own LDS reads; the kernel counts these loads itself (wait_vm).
-__device__ __forceinline__ void lds_dma16(const void *g_uniform, uint32_t lane_off, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(lane_off),
-               "s"(g_uniform)
-               : "memory", "m0");
-}
-template <int N>
-__device__ __forceinline__ void wait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// Flash-attention sweep over 64-key sub-tiles t = 0 .. nsub-1, 32 queries per wavefront.
-//
-// Software pipeline (per wavefront), step t:
-//     MFMA stream   S[t+1] = K[t+1] Q^T          then   O += V[t]^T P[t]^T
-//     VALU stream   P[t] = 2^(S[t] c - m)        then   row max of S[t+1], running-max update
-//   interleaved instruction by instruction (a hand-laid schedule), so the softmax runs in the
-//   shadow of the matrix pipe.  Steps near the diagonal take a general path (causal mask / skip).
-// K and V images ride in LDS rings (RK, RV slots) filled by LDS-direct loads issued DK resp. DV
-// steps ahead, one chunk at a time from inside the MFMA groups; one workgroup barrier per step.
-// One query block per workgroup (B/32 wavefronts); two workgroups per CU, so each SIMD holds two
-// wavefronts of different workgroups and one's barrier / load-issue time is covered by the other.
-template <int D, int B, bool DENSE, bool SCORES>
-__global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
-  constexpr int NW = B / 32;        // wavefronts per workgroup, 32 queries each
-  constexpr int SPB = B / KT;       // sub-tiles per key block
-  constexpr int IMG = KT * D * 2;   // bytes of a packed K (or V) image
-  constexpr int STAGE = 2 * IMG;    // K image + V image in the packed buffer
-  constexpr int DS = D / 16;        // k-steps of the QK^T product
-  constexpr int DB = D / 32;        // 32-row blocks of O^T
-  constexpr int DK = 2, DV = 2;                              // prefetch distances (steps)
-  constexpr int RK = DK, RV = DV + 1;                        // ring slots
-  constexpr int CH = IMG / 1024 / NW;                        // 1 KiB chunks per wavefront per image
-  // Each step issues its CH chunks of K[t+DK] first, then its CH chunks of V[t+DV].  At the top of the next
-  // step K[t+1] (issued a step ago) must have landed; the V chunks issued after it are for a later step and
-  // may still be in flight (vmcnt counts in order).
-  constexpr int VM_KEEP = CH;
-  static_assert(IMG % (1024 * NW) == 0, "image must split evenly over the wavefronts");
-  __shared__ __attribute__((aligned(1024))) char smem[(RK + RV) * IMG];
-  const uint32_t lds_k = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
-  const uint32_t lds_v = lds_k + RK * IMG;
-
-  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, c32 = lane & 31;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, kept scalar
-  // workgroup -> (XCD, strand, query block, batch).  Workgroups are dealt round-robin to the 8 XCDs by the
-  // hardware.  Every listed head is cut into 8 strands (the query blocks i with (nqb-1-i) % 8 == s, all of
-  // about equal work and each spanning short and long rows); the 8n strands g = 8*slot + s, in slot-table
-  // order, are dealt to the XCDs in contiguous runs of n, so whatever n is every XCD gets the same work and
-  // works on at most ceil(n/8)+1 heads (heads that share a KV head sit next to each other and meet in its
-  // L2).  Inside an XCD the dispatch order is rows from long to short, then strand number, then head: the
-  // heads that walk the same list for the same row are neighbours in time.
-  const int xcd = blockIdx.x & 7;
-  int rest = blockIdx.x >> 3;
-  const int b = rest / (p.n_heads * p.rgroups);
-  rest %= p.n_heads * p.rgroups;
-  // number of heads this launch really has for batch entry b (all listed ones unless the device says otherwise)
-  const int n_act = p.act_n ? __builtin_amdgcn_readfirstlane(p.act_n[b]) : p.n_heads;
-  if (n_act <= 0 || rest >= n_act * p.rgroups) return;
-  int kk = rest % n_act;  // position inside the XCD's run, enumerated strand number first, head second
-  rest /= n_act;
-  const int g0 = xcd * n_act, g1 = g0 + n_act - 1;
-  int strand = g0;
-#pragma unroll
-  for (int sn = 0; sn < 8; ++sn) {
-    const int lo = (g0 >> 3) + (sn >= (g0 & 7) ? 0 : 1), hi = (g1 >> 3) - (sn <= (g1 & 7) ? 0 : 1);
-    const int cnt = hi - lo + 1;  // heads of the run that own a strand number sn
-    if (kk >= 0 && kk < cnt) strand = (lo + kk) * 8 + sn;
-    kk -= (cnt > 0 ? cnt : 0);
-  }
-  int slot = strand >> 3;
-  if (p.act_pos) slot = __builtin_amdgcn_readfirstlane(p.act_pos[(int64_t)b * p.n_heads + slot]);
-  const int i = p.nqb - 1 - (rest * 8 + (strand & 7));
-  if (i < 0) return;  // nqb is not a multiple of 8: this strand has one row fewer
-  int head = p.head_ids[slot];
-  const int nkb = p.nqb;
-  const int hpos = p.head_pos[slot];
-  if (p.head_dev) {
-    head = __builtin_amdgcn_readfirstlane(p.head_dev[(int64_t)b * p.n_heads + hpos]);
-    if (head < 0 || head >= p.n_q_heads) return;
-  }
-  const int kvh = head / p.group;
-
-  const int tq = 32 * w + c32;  // this lane's query inside the block
-  bf16x8 qf[DS];
-  {
-    const uint16_t *qp =
-        p.q + (int64_t)b * p.q_sb + ((int64_t)i * B + tq) * p.q_st + (int64_t)head * p.q_sh + 8 * h;
-#pragma unroll
-    for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
-  }
-
-  f32x16 oacc[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-  float m = -INFINITY, l = 0.f, bs = 0.f;
-
-  int nblk;
-  const int32_t *list = nullptr;
-  if (DENSE) {
-    nblk = i + 1;
-  } else {
-    int map = p.head_map[slot];
-    if (p.head_pattern) {
-      map = __builtin_amdgcn_readfirstlane(p.head_pattern[(int64_t)b * p.n_q_heads + head]);
-      map = map >= p.n_maps ? p.n_maps - 1 : map;
-      if (map <= -2) return;
-    }
-    if (map < 0 && p.priv_idx) {
-      const int64_t lrow_id = ((int64_t)b * p.n_q_heads + head) * p.nqb + i;
-      nblk = p.priv_cnt[lrow_id];
-      nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
-      list = p.priv_idx + lrow_id * nkb;
-    } else if (map < 0) {
-      nblk = i + 1;  // list stays null: dense walk
-    } else {
-      const int64_t lrow_id = ((int64_t)b * p.n_maps + map) * p.nqb + i;
-      nblk = p.kb_cnt[lrow_id];
-      nblk = nblk < 0 ? 0 : (nblk > nkb ? nkb : nblk);
-      list = p.kb_idx + lrow_id * nkb;
-    }
-  }
-  const int nsub = nblk * SPB;
-  const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
-  float *lrow = nullptr;
-  if (SCORES) lrow = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb) * B + tq;
-
-  // key block of sub-tile t (t clamped to the sequence; list entries clamped into [0, i]: memory-safe
-  // whatever the list holds)
-  auto block_of = [&](int t) -> int {
-    int e = (t < nsub ? t : nsub - 1) / SPB;
-    if (DENSE || list == nullptr) return e;
-    const int j = list[e];
-    return j < 0 ? 0 : (j > i ? i : j);
-  };
-  // what this wavefront has to do for sub-tile `sub` of key block j: 0 all of it, 1 causal mask, 2 nothing
-  auto mode_of = [&](int j, int sub) -> int {
-    if (j != i) return 0;
-    const int klo = KT * sub, qlo = 32 * w;
-    return (klo > qlo + 31) ? 2 : ((klo + KT - 1 <= qlo) ? 0 : 1);
-  };
-  // every wavefront moves CH chunks of the image of sub-tile t (clamped) into ring slot `slot_base`
-  auto img_src = [&](int t, int j, bool is_v) -> const char * {
-    const int tt = t < nsub ? t : nsub - 1;
-    return kvbase + (int64_t)(j * SPB + tt % SPB) * STAGE + (is_v ? IMG : 0) + (w * CH) * 1024;
-  };
-  // chunk n (0 .. CH-1) of this wavefront's share of an image
-  auto issue_chunk = [&](const char *src, uint32_t slot_base, int n) {
-    lds_dma16(src + n * 1024, lane * 16, slot_base + (w * CH + n) * 1024);
-  };
-  auto issue_img = [&](int t, int j, bool is_v, uint32_t slot_base) {
-    const char *src = img_src(t, j, is_v);
-#pragma unroll
-    for (int n = 0; n < CH; ++n) issue_chunk(src, slot_base, n);
-  };
-
-  auto qk = [&](const char *kbuf, f32x16(&s)[2]) {
-    const char *kb = kbuf + lane * 16;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
-#pragma unroll
-    for (int ds = 0; ds < DS; ++ds)
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kb + (rb * DS + ds) * 1024);
-        s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ds], s[rb], 0, 0, 0);
-      }
-  };
-  // Online softmax, split in two halves that sit in different pipeline steps.
-  // tile_max: (optionally causal-masked) row max of a freshly computed S tile; moves the running max,
-  // rescales the running sums, returns alpha = 2^(m_old - m_new) for the O accumulators.
-  auto tile_max = [&](f32x16(&s)[2], int mode, int sub) -> float {
-    if (mode == 1) {
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kk = KT * sub + 32 * rb + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (kk > tq) s[rb][r] = -INFINITY;
-        }
-    }
-    float mx = fmaxf(s[0][0], s[0][1]);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int r = (rb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[rb][r], s[rb][r + 1]));
-    mx = max_xor32(mx);
-    const float m_new = lazy_max(m, mx * p.c);
-    const float alpha = fast_exp2(m - m_new);
-    m = m_new;
-    l *= alpha;
-    bs *= alpha;
-    return alpha;
-  };
-  // tile_exp: P = 2^(S*c - m) for a tile whose max is already folded into m; adds the row sums,
-  // leaves P rounded to bf16 in pb (the B operand of the PV product)
-  auto tile_exp = [&](f32x16(&s)[2], bf16x8(&pb)[4]) {
-    float rs0 = 0.f, rs1 = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      u32x4 t;
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        const int r = 8 * (ks & 1) + 2 * e2;
-        const float p0 = fast_exp2(__builtin_fmaf(s[ks >> 1][r], p.c, -m));
-        const float p1 = fast_exp2(__builtin_fmaf(s[ks >> 1][r + 1], p.c, -m));
-        rs0 += p0;
-        rs1 += p1;
-        t[e2] = pack_bf16(p0, p1);
-      }
-      pb[ks] = __builtin_bit_cast(bf16x8, t);
-    }
-    const float rs = sum_xor32(rs0 + rs1);
-    l += rs;
-    bs += rs;
-  };
-  auto rescale = [&](float alpha) {
-    if (__any(alpha != 1.f)) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-    }
-  };
-  auto pv = [&](const char *vbuf, const bf16x8(&pb)[4]) {
-    const char *vb = vbuf + lane * 16;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vb + (db * 4 + ks) * 1024);
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks], oacc[db], 0, 0, 0);
-      }
-  };
-
-  // On entry to step t: s_cur = raw S[t] (masked where needed), m / l / bs / O already moved to the
-  // running max that includes tile t.  jv = key block of the V image to fetch (tile t+DV), jk = of
-  // the K image (tile t+DK).
-  // sync_and_fill: wait until the images this step reads have landed for every wavefront, then
-  // refill the ring slots the previous step freed.
-  auto sync_and_fill = [&](int t, int jv, int jk) {
-    wait_vm<VM_KEEP>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    issue_img(t + DK, jk, false, lds_k + ((t + DK) % RK) * IMG);
-    issue_img(t + DV, jv, true, lds_v + ((t + DV) % RV) * IMG);
-  };
-  // fast step: tiles t and t+1 both off the diagonal.  One basic block up to the rescale test.
-  auto fast_step = [&](int t, int j0, int jv, int jk, f32x16(&s_cur)[2], f32x16(&s_next)[2]) {
-    // the ring refills (K for the step after next, then V for the same step) are dropped one chunk at a time
-    // into the MFMA groups below instead of going out in a burst after the barrier
-    wait_vm<VM_KEEP>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    const char *ksrc = img_src(t + DK, jk, false);
-    const uint32_t kslot = lds_k + ((t + DK) % RK) * IMG;
-    const char *vsrc = img_src(t + DV, jv, true);
-    const uint32_t vslot = lds_v + ((t + DV) % RV) * IMG;
-    const char *kb = smem + ((t + 1) % RK) * IMG + lane * 16;
-    const char *vb = smem + (RK + t % RV) * IMG + lane * 16;
-    // Hand-laid schedule: NM groups, each = one MFMA + one LDS read (PF fragments ahead) + a slice
-    // of the VALU work; nothing may cross a group boundary (sched_barrier).
-    //   groups 0 .. NQ-1   : S[t+1] += K frag * Q frag ; exp / row-sum / bf16 pack of S[t]
-    //   groups NQ .. NM-1  : O += V frag * P frag       ; row max of S[t+1], running-max update
-    constexpr int NQ = 2 * DS, NP = 4 * DB, NM = NQ + NP;
-    constexpr int PF = 4;       // LDS fragments read ahead of the MFMA that uses them
-    constexpr int MAXTAIL = 4;  // the running-max update sits this many groups before the end
-    auto frag = [&](int n) -> bf16x8 {
-      if (n < NQ) return *reinterpret_cast<const bf16x8 *>(kb + ((n % 2) * DS + n / 2) * 1024);
-      const int np = n - NQ;
-      return *reinterpret_cast<const bf16x8 *>(vb + ((np % DB) * 4 + np / DB) * 1024);
-    };
-    bf16x8 fr[PF + 1];
-    bf16x8 pb[4];
-    u32x4 pt;
-    float rs0 = 0.f, rs1 = 0.f, mx = 0.f, lval = 0.f, alpha = 1.f;
-    float xa[16], xb[16];
-#pragma unroll
-    for (int n = 0; n < PF; ++n) fr[n] = frag(n);
-#pragma unroll
-    for (int n = 0; n < NM; ++n) {
-      if (n + PF < NM) fr[(n + PF) % (PF + 1)] = frag(n + PF);
-      if (n < NQ) {
-        if (n < 2) {
-          f32x16 z;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) z[r] = 0.f;
-          s_next[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], qf[0], z, 0, 0, 0);
-        } else {
-          s_next[n % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], qf[n / 2], s_next[n % 2], 0, 0, 0);
-        }
-      }
-      // exp units u (2 scores each), three stages in consecutive groups so that no instruction waits
-      // on the one just issued: scale+shift in group g(u), exp2 in g(u)+1, row sum + bf16 pack in g(u)+2
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int gu = u * NQ / 16;
-        const int ks = u / 4, e2 = u % 4, r = 8 * (ks & 1) + 2 * e2;
-        if (gu == n) {
-          xa[u] = __builtin_fmaf(s_cur[ks >> 1][r], p.c, -m);
-          xb[u] = __builtin_fmaf(s_cur[ks >> 1][r + 1], p.c, -m);
-        }
-        if (gu + 1 == n) {
-          xa[u] = fast_exp2(xa[u]);
-          xb[u] = fast_exp2(xb[u]);
-        }
-        if (gu + 2 == n) {
-          rs0 += xa[u];
-          rs1 += xb[u];
-          pt[e2] = pack_bf16(xa[u], xb[u]);
-          if (e2 == 3) pb[ks] = __builtin_bit_cast(bf16x8, pt);
-        }
-      }
-      if (n == NQ + 2) {
-        const float rs = sum_xor32(rs0 + rs1);
-        l += rs;
-        bs += rs;
-        if (SCORES && t % SPB == SPB - 1) {  // end of key block j0: log2 of the block's exp-sum
-          lval = m + fast_log2(bs);
-          bs = 0.f;
-        }
-      }
-      {
-        constexpr int GAP = NM / (2 * CH);  // groups between two chunk loads
-        if (n % GAP == 1 && n / GAP < CH) issue_chunk(ksrc, kslot, n / GAP);
-        if (n % GAP == 1 && n / GAP >= CH && n / GAP < 2 * CH) issue_chunk(vsrc, vslot, n / GAP - CH);
-      }
-      if (n >= NQ) {
-        const int np = n - NQ;
-        oacc[np % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % (PF + 1)], pb[np / DB], oacc[np % DB], 0, 0, 0);
-        // row max of S[t+1]: 16 max3 units spread over groups 2 .. NP-1-MAXTAIL, then the running-max
-        // update MAXTAIL groups before the end (its dependent chain hides under the last MFMAs)
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          if (2 + u * (NP - 2 - MAXTAIL) / 16 != np) continue;
-          const float a0 = s_next[u / 8][2 * (u % 8)], a1 = s_next[u / 8][2 * (u % 8) + 1];
-          mx = (u == 0) ? fmaxf(a0, a1) : fmaxf(mx, fmaxf(a0, a1));
-        }
-        if (np == NP - MAXTAIL) {
-          mx = max_xor32(mx);
-          const float m_new = lazy_max(m, mx * p.c);
-          alpha = fast_exp2(m - m_new);
-          m = m_new;
-          l *= alpha;
-          bs *= alpha;
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    rescale(alpha);
-    if (SCORES && t % SPB == SPB - 1 && h == 0) lrow[(int64_t)j0 * B] = lval;
-  };
-  // general step: per-wavefront causal mask / skip near the diagonal, optional next tile
-  auto slow_step = [&](int t, int j0, int j1, int jv, int jk, f32x16(&s_cur)[2], f32x16(&s_next)[2]) {
-    sync_and_fill(t, jv, jk);
-    const char *k_next = smem + ((t + 1) % RK) * IMG;
-    const char *v_cur = smem + (RK + t % RV) * IMG;
-    const int sub = t % SPB, sub1 = (t + 1) % SPB;
-    const int mode0 = mode_of(j0, sub);
-    const int mode1 = (t + 1 < nsub) ? mode_of(j1, sub1) : 2;
-    if (mode1 != 2) qk(k_next, s_next);
-    if (mode0 != 2) {
-      bf16x8 pb[4];
-      tile_exp(s_cur, pb);
-      pv(v_cur, pb);
-    }
-    if (SCORES && sub == SPB - 1 && mode_of(j0, 0) != 2) {
-      if (h == 0) lrow[(int64_t)j0 * B] = m + fast_log2(bs);
-      bs = 0.f;
-    }
-    if (mode1 != 2) rescale(tile_max(s_next, mode1, sub1));
-  };
-
-  if (nsub > 0) {
-    // leading run of sub-tiles that lie before the first diagonal entry of the list
-    int nfast;
-    if (DENSE || list == nullptr) {
-      nfast = i * SPB;
-    } else {
-      int first = nblk;
-      for (int e = lane; e < nblk; e += 64)
-        if (list[e] >= i) first = first < e ? first : e;
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) {
-        const int o2 = __shfl_xor(first, off, 64);
-        first = first < o2 ? first : o2;
-      }
-      nfast = __builtin_amdgcn_readfirstlane(first) * SPB;
-    }
-    // fast steps need tile t+1 off the diagonal too; keep their count even (tail starts on even parity)
-    nfast = nfast > 0 ? ((nfast - 1) & ~1) : 0;
-
-    f32x16 s_a[2], s_b[2];
-    // jw[n] = key block of sub-tile t + n
-    int jw[6];
-#pragma unroll
-    for (int n = 0; n < 6; ++n) jw[n] = block_of(n);
-    // prologue: K[0 .. DK-1], V[0 .. DV-1]
-#pragma unroll
-    for (int n = 0; n < DK; ++n) {
-      if (n < DV && n < nsub) issue_img(n, jw[n], true, lds_v + (n % RV) * IMG);
-      if (n < nsub) issue_img(n, jw[n], false, lds_k + (n % RK) * IMG);
-    }
-    wait_vm<0>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    {
-      const int mode = mode_of(jw[0], 0);
-      if (mode != 2) {
-        qk(smem, s_a);
-        tile_max(s_a, mode, 0);  // O is still zero: nothing to rescale
-      }
-    }
-    int t = 0;
-    for (; t < nfast; t += 2) {
-      const int jn0 = block_of(t + 6), jn1 = block_of(t + 7);
-      fast_step(t, jw[0], jw[DV], jw[DK], s_a, s_b);
-      fast_step(t + 1, jw[1], jw[DV + 1], jw[DK + 1], s_b, s_a);
-#pragma unroll
-      for (int n = 0; n < 4; ++n) jw[n] = jw[n + 2];
-      jw[4] = jn0;
-      jw[5] = jn1;
-    }
-    for (; t < nsub; t += 2) {
-      const int jn0 = block_of(t + 6), jn1 = block_of(t + 7);
-      slow_step(t, jw[0], jw[1], jw[DV], jw[DK], s_a, s_b);
-      if (t + 1 < nsub) slow_step(t + 1, jw[1], jw[2], jw[DV + 1], jw[DK + 1], s_b, s_a);
-#pragma unroll
-      for (int n = 0; n < 4; ++n) jw[n] = jw[n + 2];
-      jw[4] = jn0;
-      jw[5] = jn1;
-    }
-    wait_vm<0>();  // drain the ring's look-ahead loads before the LDS is reused or released
-  }
-
-  // ---- output: O = O^T accumulators / l, rounded to bf16 ----
-  {
-    const float inv = (l > 0.f) ? 1.f / l : 0.f;
-    uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)i * B + tq) * p.o_st + (int64_t)head * p.o_sh;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        u32x2 t;
-        t[0] = pack_bf16(oacc[db][4 * gq] * inv, oacc[db][4 * gq + 1] * inv);
-        t[1] = pack_bf16(oacc[db][4 * gq + 2] * inv, oacc[db][4 * gq + 3] * inv);
-        *reinterpret_cast<u32x2 *>(op + 32 * db + 8 * gq + 4 * h) = t;
-      }
-  }
-
-  // ---- block-mass scores: S[i][j] = (1/B) sum_t 2^(lws[j][t] - L_t) ----
-  // Each wavefront takes 32 key blocks at a time.  Stage 1: lane <-> query, coalesced reads of the block
-  // log-sum-exps, one partial per (key block, lane) into a wavefront-private LDS tile (rows padded to 65
-  // floats).  Stage 2: lane <-> key block, the tile is read transposed and summed.  No cross-lane reduction
-  // chain and several rows of loads in flight: the workspace rows were written long ago and come from HBM.
-  if (SCORES) {
-    constexpr int TPL = B / 64, PST = 65, JU = 8;
-    constexpr int JB = (1024 + NW * 32 * PST * 4 <= (RK + RV) * IMG) ? 32 : 16;  // key blocks per tile
-    constexpr int NPART = 64 / JB, PLEN = 64 / NPART;  // stage 2: NPART lanes share a key block, PLEN entries each
-    static_assert(1024 + NW * JB * PST * 4 <= (RK + RV) * IMG, "score epilogue tiles must fit the idle rings");
-    float *lse_sh = reinterpret_cast<float *>(smem);  // [B]; the rings are idle now
-    float *part = reinterpret_cast<float *>(smem + 1024) + w * (JB * PST);
-    __syncthreads();
-    if (h == 0) lse_sh[tq] = m + fast_log2(l);
-    __threadfence();
-    __syncthreads();
-    float lt[TPL];
-#pragma unroll
-    for (int tt = 0; tt < TPL; ++tt) lt[tt] = lse_sh[lane + 64 * tt];
-    const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb) * B;
-    float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb;
-    const int jr = lane % JB, jp = lane / JB;
-    for (int j0 = w * JB; j0 <= i; j0 += NW * JB) {
-#pragma unroll
-      for (int u0 = 0; u0 < JB; u0 += JU) {
-        float x[JU][TPL];
-#pragma unroll
-        for (int u = 0; u < JU; ++u) {
-          const int j = (j0 + u0 + u <= i) ? j0 + u0 + u : i;
-#pragma unroll
-          for (int tt = 0; tt < TPL; ++tt) x[u][tt] = lblk[(int64_t)j * B + lane + 64 * tt];
-        }
-#pragma unroll
-        for (int u = 0; u < JU; ++u) {
-          float e = 0.f;
-#pragma unroll
-          for (int tt = 0; tt < TPL; ++tt) e += fast_exp2(x[u][tt] - lt[tt]);
-          part[(u0 + u) * PST + lane] = e;
-        }
-      }
-      // the tile is private to this wavefront: order its own LDS writes before its transposed reads
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      float acc = 0.f;
-#pragma unroll
-      for (int kq = 0; kq < PLEN; ++kq) acc += part[jr * PST + jp * PLEN + kq];
-      acc = sum_xor32(acc);
-      if (NPART == 4) acc += __shfl_xor(acc, 16, 64);
-      if (jp == 0 && j0 + jr <= i) srow[j0 + jr] = acc * (1.f / B);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
-    for (int j = i + 1 + w * 64 + lane; j < nkb; j += NW * 64) srow[j] = 0.f;
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// mask kernel (Alg. 2 per row, exact integers)
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t x) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
-  return x;
-}
-
-__device__ __forceinline__ uint32_t quantise24(float s) {
-  // bit tests, so the result does not depend on how the compiler treats NaN comparisons
-  const uint32_t bits = __float_as_uint(s);
-  if (bits & 0x80000000u) return 0u;         // negative (and -0, -NaN)
-  if (bits > 0x7F800000u) return 0u;         // NaN
-  if (bits >= 0x3F800000u) return 1u << 24;  // >= 1 (and +inf) clamps to 1
-  return (uint32_t)rintf(s * 16777216.f);
-}
-
-// One wavefront per (map, row).  EPL > 0: the row lives in registers (nkb <= 64*EPL);
-// EPL == 0: any nkb, the row is re-read from memory in every pass.
-template <int EPL>
-__global__ __launch_bounds__(256) void mask_kernel(const float *__restrict__ scores, int n_rows_total, int nqb,
-                                                   int nkb, uint32_t gq, int32_t *__restrict__ kb_idx,
-                                                   int32_t *__restrict__ kb_cnt, uint64_t *__restrict__ bitmask,
-                                                   const int32_t *__restrict__ route) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= n_rows_total) return;
-  const int i = row % nqb;
-  // route (optional, [n_maps]): the map whose lists this map's rows become, negative = leave this map out
-  int64_t orow = row;
-  if (route) {
-    const int dst = route[row / nqb];
-    if (dst < 0) return;
-    orow = (int64_t)dst * nqb + i;
-  }
-  const float *src = scores + (int64_t)row * nkb;
-  const int nchunk = (i >> 6) + 1;  // 64-wide chunks that hold valid key blocks
-  uint32_t u[EPL > 0 ? EPL : 1];
-  auto get = [&](int e) -> uint32_t {
-    if (EPL > 0) return u[e];
-    const int j = e * 64 + lane;
-    return (j <= i) ? quantise24(src[j]) : 0u;
-  };
-  if (EPL > 0) {
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      const int j = e * 64 + lane;
-      u[e] = (j <= i) ? quantise24(src[j]) : 0u;
-    }
-  }
-  auto sum_ge = [&](uint32_t v) -> uint64_t {
-    uint64_t part = 0;
-    if (EPL > 0) {
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) part += (u[e] >= v) ? u[e] : 0u;
-    } else {
-      for (int e = 0; e < nchunk; ++e) {
-        const uint32_t x = get(e);
-        part += (x >= v) ? x : 0u;
-      }
-    }
-    return wave_sum_u64(part);
-  };
-  const uint64_t tot = sum_ge(1u);
-  uint32_t vstar = 0xFFFFFFFFu;  // nothing reaches it: only forced blocks when tot == 0
-  uint64_t need = 0;
-  if (tot > 0) {
-    uint64_t T = ((uint64_t)gq * tot + 16777215ull) >> 24;  // least integer prefix sum that reaches gamma
-    if (T < 1) T = 1;
-    uint32_t lo = 1u, hi = 16777217u;  // sum_ge(lo) >= T > sum_ge(hi)
-    while (hi - lo > 1u) {
-      const uint32_t mid = lo + ((hi - lo) >> 1);
-      if (sum_ge(mid) >= T) lo = mid; else hi = mid;
-    }
-    vstar = lo;
-    const uint64_t above = sum_ge(vstar + 1u);
-    need = (T - above + vstar - 1) / vstar;  // ties taken, lowest key block first
-  }
-  int32_t *out = kb_idx + orow * nkb;
-  const int nwords = (nkb + 63) >> 6;
-  const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  uint32_t ties_before = 0, n_out = 0;
-  const int nch_all = EPL > 0 ? EPL : nwords;
-  for (int e = 0; e < nch_all; ++e) {
-    if (e >= nwords) break;
-    const int j = e * 64 + lane;
-    uint32_t x = 0;
-    if (EPL > 0) {
-#pragma unroll
-      for (int ee = 0; ee < EPL; ++ee)
-        if (ee == e) x = u[ee];
-    } else {
-      x = (e < nchunk) ? get(e) : 0u;
-    }
-    const bool tie = (j <= i) && (x == vstar);
-    const uint64_t tmask = __ballot(tie);
-    const uint32_t trank = ties_before + __popcll(tmask & lt);
-    ties_before += __popcll(tmask);
-    const bool sel = (j <= i) && ((x > vstar && vstar != 0xFFFFFFFFu) || (tie && trank < need) || j == 0 || j == i);
-    const uint64_t smask = __ballot(sel);
-    if (sel) out[n_out + __popcll(smask & lt)] = j;
-    n_out += __popcll(smask);
-    if (bitmask && lane == 0) bitmask[orow * nwords + e] = smask;
-  }
-  for (int pos = n_out + lane; pos < nkb; pos += 64) out[pos] = -1;
-  if (lane == 0) kb_cnt[orow] = (int32_t)n_out;
-}
-
-// ---------------------------------------------------------------------------------------------
-// pattern construction as printed in the paper (Sec. 5.2 "Sparse Attention Computation" and
-// "Pivotal Pattern Construction"; Alg. 2): block-mean logits -> row softmax -> one selection over
-// the flattened, globally normalised map
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float bf16_bits_to_float(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
-
-struct PoolParams {
-  const uint16_t *q, *k;
-  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
-  int nqb, group, n_heads, n_kv_heads;
-  int row0, n_rows;  // query-block rows row0 .. row0 + n_rows - 1 are wanted
-  float *qsum;       // [b][n][n_rows][D]   sum of the block's queries
-  float *ksumT;      // [b][kvh][D][nqb]    sum of the block's keys, block index fastest
-  float *diag;       // [b][n][n_rows]      sum over the diagonal block's causal entries of q_t . k_s
-  float *out;        // [b][n][n_rows][nqb] row softmax of the block-mean logits
-  float c_full, c_diag;
-  const int32_t *head_dev;  // optional [b][n_heads]: head of listed position n chosen on the device, < 0 = empty
-  int32_t head_ids[SP_MAX_HEADS];
-};
-__device__ __forceinline__ int pool_head(const PoolParams &p, int b, int n) {
-  return p.head_dev ? p.head_dev[(int64_t)b * p.n_heads + n] : p.head_ids[n];
-}
-
-// The average of q_t . k_s over a full block is (sum_t q_t) . (sum_s k_s) / B^2, so the block-mean
-// logits need only per-block sums of Q and K.  One thread per head dimension, one block per workgroup.
-template <int D, int B>
-__global__ __launch_bounds__(D) void key_pool_kernel(PoolParams p) {
-  const int i = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z, e = threadIdx.x;
-  const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)i * B * p.k_st + (int64_t)kvh * p.k_sh + e;
-  float run = 0.f;
-#pragma unroll 8
-  for (int t = 0; t < B; ++t) run += bf16_bits_to_float(kp[(int64_t)t * p.k_st]);
-  p.ksumT[(((int64_t)b * p.n_kv_heads + kvh) * D + e) * p.nqb + i] = run;
-}
-
-// Query sums of the wanted rows and, for the diagonal block (which keeps s <= t only), the sum
-// sum_t q_t . (sum_{s<=t} k_s) from a running key sum walked once.
-template <int D, int B>
-__global__ __launch_bounds__(D) void query_pool_kernel(PoolParams p) {
-  const int r = blockIdx.x, n = blockIdx.y, b = blockIdx.z, e = threadIdx.x;
-  const int i = p.row0 + r;
-  const int head = pool_head(p, b, n);
-  if (head < 0) return;
-  const uint16_t *qp = p.q + (int64_t)b * p.q_sb + (int64_t)i * B * p.q_st + (int64_t)head * p.q_sh + e;
-  const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)i * B * p.k_st + (int64_t)(head / p.group) * p.k_sh + e;
-  float run = 0.f, qs = 0.f, acc = 0.f;
-#pragma unroll 8
-  for (int t = 0; t < B; ++t) {
-    const float kk = bf16_bits_to_float(kp[(int64_t)t * p.k_st]);
-    const float qq = bf16_bits_to_float(qp[(int64_t)t * p.q_st]);
-    run += kk;
-    qs += qq;
-    acc = fmaf(qq, run, acc);
-  }
-  const int64_t hr = ((int64_t)b * p.n_heads + n) * p.n_rows + r;
-  p.qsum[hr * D + e] = qs;
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  if constexpr (D == 64) {
-    if (e == 0) p.diag[hr] = acc;
-  } else {
-    __shared__ float part[D / 64];
-    if ((e & 63) == 0) part[e >> 6] = acc;
-    __syncthreads();
-    if (e == 0) {
-      float s = 0.f;
-#pragma unroll
-      for (int w = 0; w < D / 64; ++w) s += part[w];
-      p.diag[hr] = s;
-    }
-  }
-}
-
-// Four query-block rows per workgroup: thread j forms the four pooled dot products against key block j
-// (block index fastest in ksumT, so the loads coalesce), then one wavefront per row applies the row
-// softmax in place (Alg. 2, first step; Alg. 3's estimate when only the last row is asked for).
-// Entries beyond the diagonal are written as 0.
-template <int D>
-__global__ __launch_bounds__(256) void mean_logit_softmax_kernel(PoolParams p) {
-  constexpr int R = 4;
-  __shared__ float qs[R][D];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int r0 = blockIdx.x * R;
-  const int64_t hb = blockIdx.y;
-  const int b = (int)(hb / p.n_heads), n = (int)(hb % p.n_heads);
-  const int nqb = p.nqb;
-  const int head = pool_head(p, b, n);
-  if (head < 0) return;
-  for (int x = tid; x < R * D; x += 256) {
-    const int r = x / D, e = x % D;
-    qs[r][e] = (r0 + r < p.n_rows) ? p.qsum[((hb * p.n_rows) + r0 + r) * D + e] : 0.f;
-  }
-  __syncthreads();
-  const float *kT = p.ksumT + ((int64_t)b * p.n_kv_heads + head / p.group) * D * nqb;
-  const int rmax = min(r0 + R - 1, p.n_rows - 1);
-  const int imax = p.row0 + rmax;
-  for (int j = tid; j <= imax; j += 256) {
-    float acc[R] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-    for (int e = 0; e < D; ++e) {
-      const float kv = kT[(int64_t)e * nqb + j];
-#pragma unroll
-      for (int r = 0; r < R; ++r) acc[r] = fmaf(qs[r][e], kv, acc[r]);
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int i = p.row0 + r0 + r;
-      if (r0 + r < p.n_rows && j <= i)
-        p.out[(hb * p.n_rows + r0 + r) * nqb + j] = (j < i) ? acc[r] * p.c_full : p.diag[hb * p.n_rows + r0 + r] * p.c_diag;
-    }
-  }
-  __syncthreads();
-  if (r0 + w >= p.n_rows) return;
-  const int i = p.row0 + r0 + w;
-  float *row = p.out + (hb * p.n_rows + r0 + w) * nqb;
-  float mx = -INFINITY;
-  for (int j = lane; j <= i; j += 64) mx = fmaxf(mx, row[j]);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-  float den = 0.f;
-  for (int j = lane; j <= i; j += 64) den += expf(row[j] - mx);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off, 64);
-  for (int j = lane; j < nqb; j += 64) row[j] = (j <= i) ? expf(row[j] - mx) / den : 0.f;
-}
-
-// ---- Alg. 3 (Determine Sparse Pattern): Jensen-Shannon gate ------------------------------------
-struct GateParams {
-  const float *a_hat;     // [b][n][nkb] estimates of the listed heads
-  float *dist;            // [b][n][2]   d_sparse, d_sim
-  int32_t *head_pattern;  // [b][n_q_heads], entry of each listed head written
-  int nkb, n_heads, n_q_heads;
-  float delta, tau;
-  int32_t head_ids[SP_MAX_HEADS];
-  int32_t ref_pos[SP_MAX_HEADS];     // position of the head whose estimate is the representative, or -1
-  int32_t shared_map[SP_MAX_HEADS];  // value written when the pattern is shared
-};
-
-// x ln(x/m) + y ln(y/m), m = (x+y)/2: one entry's contribution to 2*JSD, never negative
-__device__ __forceinline__ double js_term(double x, double y) {
-  const double m = 0.5 * (x + y);
-  double t = 0.0;
-  if (x > 0.0) t += x * log(x / m);
-  if (y > 0.0) t += y * log(y / m);
-  return t;
-}
-// sqrt(JSD(a || ref)) over n entries, natural logarithm, fp64; ref == nullptr: the uniform distribution.
-// Called by a whole wavefront; every lane returns the result.
-__device__ __forceinline__ double js_distance_wave(const float *a, const float *ref, int n, int lane) {
-  const double u = 1.0 / (double)n;
-  double sum = 0.0;
-  for (int j = lane; j < n; j += 64) sum += js_term((double)a[j], ref ? (double)ref[j] : u);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
-  const double jsd = 0.5 * sum;
-  return sqrt(jsd > 0.0 ? jsd : 0.0);
-}
-
-// Alg. 3's gate for the listed heads: one wavefront per (head, batch entry).
-__global__ __launch_bounds__(64) void js_gate_kernel(GateParams p) {
-  const int n = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-  const float *a = p.a_hat + ((int64_t)b * p.n_heads + n) * p.nkb;
-  const int rp = p.ref_pos[n];
-  const double d_sparse = js_distance_wave(a, nullptr, p.nkb, lane);
-  const double d_sim = (rp >= 0) ? js_distance_wave(a, p.a_hat + ((int64_t)b * p.n_heads + rp) * p.nkb, p.nkb, lane) : 0.0;
-  if (lane == 0) {
-    const int64_t hb = (int64_t)b * p.n_heads + n;
-    p.dist[hb * 2] = (float)d_sparse;
-    p.dist[hb * 2 + 1] = (float)d_sim;
-    const bool shared = d_sparse < (double)p.delta && d_sim < (double)p.tau;
-    p.head_pattern[(int64_t)b * p.n_q_heads + p.head_ids[n]] = shared ? p.shared_map[n] : -1;
-  }
-}
-
-// ---- dynamic pivotal pattern dictionary (Sec. 5.2; Alg. 1 with Alg. 3 and Alg. 4) ----------------
-// Roles written per (batch entry, head): c >= 0 shares cluster c's dictionary pattern, -1 falls back
-// (dense, no update), -2 is elected pivot of its cluster in this layer (dense + pattern construction).
-struct ElectParams {
-  const float *a_hat;   // [b][Hq][nkb] last-row estimates of every head
-  float *dist;          // [b][Hq][2]
-  int32_t *role;        // [b][Hq]
-  int32_t *pivot_head;  // [b][n_slots] head elected for the slot's cluster in this layer, or -1
-  int32_t *route;       // [b][n_slots] dictionary map (b * n_clusters + c) the slot's lists go to, or -1
-  int32_t *act_n;       // [b] number of slots that elected a pivot
-  int32_t *act_pos;     // [b][n_slots] those slots, ascending
-  // the heads of the role-driven attention launch, split by weight class so that each class can be spread
-  // evenly over the XCDs: positions (in that launch's slot table) of the heads that share a list, and of the
-  // heads that fall back
-  int32_t *shared_n, *shared_pos, *fallback_n, *fallback_pos;  // [b], [b][n_launch]
-  int n_launch;
-  int32_t launch_head[SP_MAX_HEADS];  // the launch's slot table: query head of each position
-  int32_t *valid;       // dictionary [b][n_clusters]
-  float *a_tilde;       // dictionary [b][n_clusters][nkb]
-  int nkb, n_q_heads, n_slots, n_clusters;
-  float delta, tau;
-  int32_t head_cluster[SP_MAX_HEADS];  // global cluster id or -1
-  int32_t head_slot[SP_MAX_HEADS];     // slot of the head's cluster, or -1
-  int32_t slot_cluster[SP_MAX_HEADS];
-};
-
-// One workgroup per batch entry.  Heads are taken in ascending order as in Alg. 1: a cluster without a
-// dictionary entry elects its first head that passes the sparsity test (there is no representative to
-// compare with yet); every other head is tested against the entry's representative, or against the
-// estimate of the pivot elected a moment ago.
-__global__ __launch_bounds__(1024) void elect_kernel(ElectParams p) {
-  __shared__ double ds[SP_MAX_HEADS];
-  __shared__ int piv[SP_MAX_HEADS];
-  __shared__ int had[SP_MAX_HEADS];
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const float *ah = p.a_hat + (int64_t)b * p.n_q_heads * p.nkb;
-  for (int h = w; h < p.n_q_heads; h += 16) {
-    const double d = js_distance_wave(ah + (int64_t)h * p.nkb, nullptr, p.nkb, lane);
-    if (lane == 0) ds[h] = d;
-  }
-  __syncthreads();
-  if (tid < p.n_slots) {
-    const int c = p.slot_cluster[tid];
-    const int v = p.valid[(int64_t)b * p.n_clusters + c];
-    int first = -1;
-    if (!v && 0.0 < (double)p.tau)
-      for (int h = p.n_q_heads - 1; h >= 0; --h)
-        if (p.head_cluster[h] == c && ds[h] < (double)p.delta) first = h;
-    piv[tid] = first;
-    had[tid] = v;
-    p.pivot_head[(int64_t)b * p.n_slots + tid] = first;
-    p.route[(int64_t)b * p.n_slots + tid] = first >= 0 ? b * p.n_clusters + c : -1;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    int na = 0;
-    for (int s2 = 0; s2 < p.n_slots; ++s2)
-      if (piv[s2] >= 0) p.act_pos[(int64_t)b * p.n_slots + na++] = s2;
-    p.act_n[b] = na;
-  }
-  for (int h = w; h < p.n_q_heads; h += 16) {
-    const int c = p.head_cluster[h], s = p.head_slot[h];
-    int role = -1;
-    double d_sim = 0.0;
-    if (c >= 0) {
-      if (piv[s] == h) {
-        role = -2;
-      } else {
-        // heads met before the pivot of a new entry saw an empty dictionary: no representative for them
-        const float *ref = had[s] ? p.a_tilde + ((int64_t)b * p.n_clusters + c) * p.nkb
-                                  : (piv[s] >= 0 && piv[s] < h ? ah + (int64_t)piv[s] * p.nkb : nullptr);
-        if (ref) {
-          d_sim = js_distance_wave(ah + (int64_t)h * p.nkb, ref, p.nkb, lane);
-          if (ds[h] < (double)p.delta && d_sim < (double)p.tau) role = c;
-        }
-      }
-    }
-    if (lane == 0) {
-      p.role[(int64_t)b * p.n_q_heads + h] = role;
-      p.dist[((int64_t)b * p.n_q_heads + h) * 2] = (float)ds[h];
-      p.dist[((int64_t)b * p.n_q_heads + h) * 2 + 1] = (float)d_sim;
-    }
-  }
-  __syncthreads();  // every read of the old representatives is done, every role is written
-  if (tid == 0) {
-    int ns = 0, nf = 0;
-    for (int pos = 0; pos < p.n_launch; ++pos) {
-      const int r = p.role[(int64_t)b * p.n_q_heads + p.launch_head[pos]];
-      if (r >= 0) p.shared_pos[(int64_t)b * p.n_launch + ns++] = pos;
-      if (r == -1) p.fallback_pos[(int64_t)b * p.n_launch + nf++] = pos;
-    }
-    p.shared_n[b] = ns;
-    p.fallback_n[b] = nf;
-  }
-  for (int s = 0; s < p.n_slots; ++s) {
-    if (piv[s] < 0) continue;
-    const int c = p.slot_cluster[s];
-    float *dst = p.a_tilde + ((int64_t)b * p.n_clusters + c) * p.nkb;
-    const float *src = ah + (int64_t)piv[s] * p.nkb;
-    for (int j = tid; j < p.nkb; j += 1024) dst[j] = src[j];
-    if (tid == 0) p.valid[(int64_t)b * p.n_clusters + c] = 1;
-  }
-}
-
-// Splits the heads of a role-driven attention launch into the two weight classes (sharing a list / falling
-// back) so that each class can be spread evenly over the XCDs; positions refer to the launch's slot table.
-struct ClassifyParams {
-  const int32_t *role;  // [b][n_q_heads]
-  int32_t *shared_n, *shared_pos, *fallback_n, *fallback_pos;  // [b], [b][n_launch]
-  int n_q_heads, n_launch;
-  int32_t launch_head[SP_MAX_HEADS];
-};
-__global__ __launch_bounds__(64) void classify_heads_kernel(ClassifyParams p) {
-  const int b = blockIdx.x;
-  if (threadIdx.x != 0) return;
-  int ns = 0, nf = 0;
-  for (int pos = 0; pos < p.n_launch; ++pos) {
-    const int r = p.role[(int64_t)b * p.n_q_heads + p.launch_head[pos]];
-    if (r >= 0) p.shared_pos[(int64_t)b * p.n_launch + ns++] = pos;
-    if (r == -1) p.fallback_pos[(int64_t)b * p.n_launch + nf++] = pos;
-  }
-  p.shared_n[b] = ns;
-  p.fallback_n[b] = nf;
-}
-
-// ---- Alg. 2 over the flattened map, exact integers -------------------------------------------
-// With u = the 24-bit score, T = ceil(gamma_q * total / 2^24): the kept set is every entry above
-// a threshold value v* plus the first `need` entries equal to v* in flat (row-major) order, where v*
-// is the largest value with sum_{u >= v*} u >= T.  v* is found by two 12-bit histogram passes
-// (sums of u per bin), the ties are ranked by a per-row count and a prefix sum over rows.
-constexpr int GS_BINS = 4104;  // 4097 used by the first pass (u can equal 2^24), padded
-struct GselState {
-  uint64_t T, above, need;
-  uint32_t bin_hi, vstar;
-  uint32_t pad[8];
-};
-static_assert(sizeof(GselState) == 64, "GselState layout");
-
-struct GselView {
-  unsigned long long *hist1, *hist2;
-  GselState *state;
-  uint32_t *row_ties, *row_before;
-};
-// Shape of the maps a selection runs over.  A causal block map is n x n with only j <= row present; a plain
-// vector of length n_rows * n_cols is a rectangular map whose row-major order is the vector's order.
-struct GselGeom {
-  int n_rows, n_cols;
-  int tri;              // 1: entries j <= row only; 0: all n_cols entries of a row
-  const int32_t *role;  // optional [n_maps / per_head]: a map is processed only if its owner's entry is -1
-  int per_head;
-};
-__device__ __forceinline__ int gsel_width(const GselGeom &g, int row) { return g.tri ? row + 1 : g.n_cols; }
-__device__ __forceinline__ bool gsel_skip(const GselGeom &g, int map) {
-  return g.role != nullptr && g.role[map / g.per_head] != -1;
-}
-__host__ __device__ inline size_t gsel_map_bytes(int n_rows) {
-  return (size_t)2 * GS_BINS * 8 + sizeof(GselState) + (((size_t)n_rows * 8 + 255) / 256) * 256;
-}
-__device__ __forceinline__ GselView gsel_view(char *scratch, int map, int nqb) {
-  char *base = scratch + (size_t)map * gsel_map_bytes(nqb);
-  GselView v;
-  v.hist1 = reinterpret_cast<unsigned long long *>(base);
-  v.hist2 = v.hist1 + GS_BINS;
-  v.state = reinterpret_cast<GselState *>(v.hist2 + GS_BINS);
-  v.row_ties = reinterpret_cast<uint32_t *>(v.state + 1);
-  v.row_before = v.row_ties + nqb;
-  return v;
-}
-
-__global__ __launch_bounds__(256) void gsel_zero_kernel(char *scratch, GselGeom g) {
-  GselView v = gsel_view(scratch, blockIdx.x, g.n_rows);
-  for (int x = threadIdx.x; x < 2 * GS_BINS; x += 256) v.hist1[x] = 0ull;
-}
-
-template <int PASS>
-__global__ __launch_bounds__(256) void gsel_hist_kernel(const float *__restrict__ scores, GselGeom g, char *scratch) {
-  __shared__ unsigned long long h[GS_BINS];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int map = blockIdx.y;
-  if (gsel_skip(g, map)) return;
-  GselView v = gsel_view(scratch, map, g.n_rows);
-  for (int x = tid; x < GS_BINS; x += 256) h[x] = 0ull;
-  __syncthreads();
-  const uint32_t bin_hi = (PASS == 2) ? v.state->bin_hi : 0u;
-  unsigned long long low = 0ull;  // first pass: bin 0 holds most of a softmaxed map; keep it out of the LDS atomics
-  for (int row = blockIdx.x * 4 + w; row < g.n_rows; row += gridDim.x * 4) {
-    const float *src = scores + ((int64_t)map * g.n_rows + row) * g.n_cols;
-    const int width = gsel_width(g, row);
-    for (int j = lane; j < width; j += 64) {
-      const uint32_t u = quantise24(src[j]);
-      if (PASS == 1) {
-        const uint32_t bin = u >> 12;
-        if (bin == 0)
-          low += u;
-        else
-          atomicAdd(&h[bin], (unsigned long long)u);
-      } else if (u != 0u && (u >> 12) == bin_hi) {
-        atomicAdd(&h[u & 4095u], (unsigned long long)u);
-      }
-    }
-  }
-  if (PASS == 1) {
-    low = wave_sum_u64(low);
-    if (lane == 0 && low) atomicAdd(&h[0], low);
-  }
-  __syncthreads();
-  unsigned long long *gh = (PASS == 1) ? v.hist1 : v.hist2;
-  for (int x = tid; x < GS_BINS; x += 256)
-    if (h[x]) atomicAdd(&gh[x], h[x]);
-}
-
-// One workgroup of 1024 threads per map.  Thread t owns bins [5t, 5t+5); a suffix sum over threads
-// locates the bin in which the running sum from the top first reaches the target.
-template <int PASS>
-__global__ __launch_bounds__(1024) void gsel_scan_kernel(char *scratch, GselGeom g, uint32_t gq) {
-  __shared__ unsigned long long wt[16];
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  if (gsel_skip(g, blockIdx.x)) return;
-  GselView v = gsel_view(scratch, blockIdx.x, g.n_rows);
-  const unsigned long long *hist = (PASS == 1) ? v.hist1 : v.hist2;
-  constexpr int NB = (PASS == 1) ? 4097 : 4096;
-  unsigned long long mine[5], sum = 0ull;
-#pragma unroll
-  for (int x = 0; x < 5; ++x) {
-    const int bin = 5 * t + x;
-    mine[x] = (bin < NB) ? hist[bin] : 0ull;
-    sum += mine[x];
-  }
-  unsigned long long incl = sum;  // sum over lanes >= this one
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const unsigned long long y = __shfl_down(incl, off, 64);
-    if (lane + off < 64) incl += y;
-  }
-  if (lane == 0) wt[w] = incl;
-  __syncthreads();
-  unsigned long long above = incl - sum, tot = 0ull;
-  for (int x = 0; x < 16; ++x) {
-    tot += wt[x];
-    if (x > w) above += wt[x];
-  }
-  unsigned long long T;
-  if (PASS == 1) {
-    const unsigned long long th = tot >> 24, tl = tot & 0xFFFFFFull;
-    T = (unsigned long long)gq * th + (((unsigned long long)gq * tl + 0xFFFFFFull) >> 24);  // ceil(gq * tot / 2^24)
-    if (T < 1) T = 1;
-    if (tot == 0ull) {
-      if (t == 0) {
-        v.state->T = 0;
-        v.state->above = 0;
-        v.state->need = 0;
-        v.state->bin_hi = 0xFFFFFFFFu;
-        v.state->vstar = 0xFFFFFFFFu;  // nothing reaches it
-      }
-      return;
-    }
-  } else {
-    if (v.state->vstar == 0xFFFFFFFFu && v.state->bin_hi == 0xFFFFFFFFu) return;  // empty map
-    T = v.state->T - v.state->above;
-  }
-  if (above < T && T <= above + sum) {  // exactly one thread
-    unsigned long long a = above;
-    for (int x = 4; x >= 0; --x) {
-      if (a + mine[x] >= T) {
-        const uint32_t bin = (uint32_t)(5 * t + x);
-        if (PASS == 1) {
-          v.state->T = T;
-          v.state->above = a;
-          v.state->bin_hi = bin;
-          v.state->vstar = 0u;
-        } else {
-          const uint32_t vs = (v.state->bin_hi << 12) | bin;
-          const unsigned long long gt = v.state->above + a;  // sum of everything above v*
-          v.state->vstar = vs;
-          v.state->need = (v.state->T - gt + vs - 1) / vs;
-        }
-        break;
-      }
-      a += mine[x];
-    }
-  }
-}
-
-__global__ __launch_bounds__(256) void gsel_row_ties_kernel(const float *__restrict__ scores, GselGeom g, char *scratch) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
-  if (row >= g.n_rows || gsel_skip(g, map)) return;
-  GselView v = gsel_view(scratch, map, g.n_rows);
-  const uint32_t vstar = v.state->vstar;
-  const float *src = scores + ((int64_t)map * g.n_rows + row) * g.n_cols;
-  const int width = gsel_width(g, row);
-  uint32_t n = 0;
-  for (int j = lane; j < width; j += 64) n += (quantise24(src[j]) == vstar) ? 1u : 0u;
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) n += __shfl_xor(n, off, 64);
-  if (lane == 0) v.row_ties[row] = n;
-}
-
-// exclusive prefix sum of row_ties over the rows of one map (flat order = row-major)
-__global__ __launch_bounds__(1024) void gsel_row_scan_kernel(GselGeom g, char *scratch) {
-  __shared__ uint32_t wt[16];
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  if (gsel_skip(g, blockIdx.x)) return;
-  const int nqb = g.n_rows;
-  GselView v = gsel_view(scratch, blockIdx.x, nqb);
-  const int per = (nqb + 1023) / 1024;
-  const int r0 = t * per, r1 = min(r0 + per, nqb);
-  uint32_t sum = 0;
-  for (int r = r0; r < r1; ++r) sum += v.row_ties[r];
-  uint32_t incl = sum;  // sum over lanes <= this one
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t y = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += y;
-  }
-  if (lane == 63) wt[w] = incl;
-  __syncthreads();
-  uint32_t before = incl - sum;
-  for (int x = 0; x < w; ++x) before += wt[x];
-  for (int r = r0; r < r1; ++r) {
-    v.row_before[r] = before;
-    before += v.row_ties[r];
-  }
-}
-
-// one wavefront per row: ascending list of the kept key blocks (+ sink and diagonal when forced)
-__global__ __launch_bounds__(256) void gsel_emit_kernel(const float *__restrict__ scores, GselGeom g, char *scratch,
-                                                        int forced, int32_t *__restrict__ kb_idx,
-                                                        int32_t *__restrict__ kb_cnt,
-                                                        const int32_t *__restrict__ route) {
-  const int lane = threadIdx.x & 63;
-  const int nqb = g.n_rows;
-  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
-  if (i >= nqb) return;
-  int omap = map;
-  if (route) {
-    omap = route[map];
-    if (omap < 0) return;
-  }
-  GselView v = gsel_view(scratch, map, nqb);
-  const uint32_t vstar = v.state->vstar;
-  const uint64_t need = v.state->need;
-  const uint64_t before = v.row_before[i];
-  const float *src = scores + ((int64_t)map * nqb + i) * nqb;
-  int32_t *out = kb_idx + ((int64_t)omap * nqb + i) * nqb;
-  const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  uint32_t ties_seen = 0, n_out = 0;
-  for (int j0 = 0; j0 <= i; j0 += 64) {
-    const int j = j0 + lane;
-    const uint32_t x = (j <= i) ? quantise24(src[j]) : 0u;
-    const bool tie = (j <= i) && (x == vstar);
-    const uint64_t tmask = __ballot(tie);
-    const uint64_t trank = before + ties_seen + __popcll(tmask & lt);
-    ties_seen += __popcll(tmask);
-    const bool sel = (j <= i) && ((x > vstar && vstar != 0xFFFFFFFFu) || (tie && trank < need) ||
-                                  (forced && (j == 0 || j == i)));
-    const uint64_t smask = __ballot(sel);
-    if (sel) out[n_out + __popcll(smask & lt)] = j;
-    n_out += __popcll(smask);
-  }
-  for (int pos = n_out + lane; pos < nqb; pos += 64) out[pos] = -1;
-  if (lane == 0) kb_cnt[(int64_t)omap * nqb + i] = (int32_t)n_out;
-}
-
-// Selection over plain vectors (rectangular geometry): per (map, row) two flags instead of a list:
-// bit 0 = some entry of the row is kept, bit 1 = some entry other than the row's first is kept.
-__global__ __launch_bounds__(256) void gsel_emit_flags_kernel(const float *__restrict__ scores, GselGeom g, char *scratch,
-                                                              int32_t *__restrict__ flags) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
-  if (row >= g.n_rows || gsel_skip(g, map)) return;
-  GselView v = gsel_view(scratch, map, g.n_rows);
-  const uint32_t vstar = v.state->vstar;
-  const uint64_t need = v.state->need;
-  const uint64_t before = v.row_before[row];
-  const float *src = scores + ((int64_t)map * g.n_rows + row) * g.n_cols;
-  const int width = gsel_width(g, row);
-  const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  uint32_t ties_seen = 0;
-  int any = 0, any_after_first = 0;
-  for (int j0 = 0; j0 < width; j0 += 64) {
-    const int j = j0 + lane;
-    const uint32_t x = (j < width) ? quantise24(src[j]) : 0u;
-    const bool tie = (j < width) && (x == vstar);
-    const uint64_t tmask = __ballot(tie);
-    const uint64_t trank = before + ties_seen + __popcll(tmask & lt);
-    ties_seen += __popcll(tmask);
-    const bool sel = (j < width) && ((x > vstar && vstar != 0xFFFFFFFFu) || (tie && trank < need));
-    const uint64_t smask = __ballot(sel);
-    any |= smask != 0ull;
-    any_after_first |= (j0 == 0 ? (smask & ~1ull) : smask) != 0ull;
-  }
-  if (lane == 0) flags[(int64_t)map * g.n_rows + row] = any | (any_after_first << 1);
-}
-
-// ---- Search Vertical Slash Pattern (Alg. 5) ------------------------------------------------------
-// Q_hat = the last `block` queries.  Their raw dot products with every key go to a workspace slab
-// X[b][n][t][s] (fp32), three memory-bound passes turn it into the normalised vertical sums a_v[s] and
-// slash sums a_s[t - s], the vector selection above keeps the shortest prefixes reaching gamma, and the kept
-// keys / offsets become per-row key-block lists.
-struct VsParams {
-  const uint16_t *q, *k;
-  int64_t q_sb, q_st, q_sh, k_sb, k_st, k_sh;
-  int seq, group, n_heads, n_q_heads;
-  float c;               // softmax scale * log2(e)
-  float *x;              // [b][n][B][seq]
-  float *stats;          // [b][n][B][2]  row max (log2 domain) and 1 / row sum
-  float *sums;           // [b][n][2][seq] a_v then a_s
-  const int32_t *role;   // optional [b][n_q_heads]: only heads whose entry is -1 are processed
-  int32_t head_ids[SP_MAX_HEADS];
-};
-__device__ __forceinline__ bool vs_skip(const VsParams &p, int b, int n) {
-  return p.role != nullptr && p.role[(int64_t)b * p.n_q_heads + p.head_ids[n]] != -1;
-}
-
-// X = Q_hat K^T with the queries as MFMA rows and the keys as columns, so that one accumulator register
-// holds 32 consecutive keys of one query across the lanes and the stores coalesce.  A workgroup takes 128
-// keys (32 per wavefront) against all B queries; operands come straight from the caller's Q and K.
-template <int D, int B>
-__global__ __launch_bounds__(256) void vs_logits_kernel(VsParams p) {
-  constexpr int DS = D / 16;
-  const int n = blockIdx.y, b = blockIdx.z;
-  if (vs_skip(p, b, n)) return;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, c = lane & 31;
-  const int head = p.head_ids[n];
-  const int s0 = blockIdx.x * 128 + 32 * w;
-  const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)(s0 + c) * p.k_st + (int64_t)(head / p.group) * p.k_sh + 8 * h;
-  bf16x8 kf[DS];
-#pragma unroll
-  for (int ds = 0; ds < DS; ++ds) kf[ds] = *reinterpret_cast<const bf16x8 *>(kp + 16 * ds);
-  float *xo = p.x + (((int64_t)b * p.n_heads + n) * B) * p.seq + s0 + c;
-#pragma unroll
-  for (int qt = 0; qt < B / 32; ++qt) {
-    const uint16_t *qp = p.q + (int64_t)b * p.q_sb + (int64_t)(p.seq - B + 32 * qt + c) * p.q_st +
-                         (int64_t)head * p.q_sh + 8 * h;
-    f32x16 acc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-#pragma unroll
-    for (int ds = 0; ds < DS; ++ds) {
-      const bf16x8 qf = *reinterpret_cast<const bf16x8 *>(qp + 16 * ds);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ds], acc, 0, 0, 0);
-    }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int t = 32 * qt + 8 * (r >> 2) + 4 * h + (r & 3);
-      xo[(int64_t)t * p.seq] = acc[r];
-    }
-  }
-}
-
-// causal softmax statistics of each of the B query rows: one workgroup per row
-template <int B>
-__global__ __launch_bounds__(256) void vs_rowstats_kernel(VsParams p) {
-  __shared__ float red[4];
-  const int t = blockIdx.x, n = blockIdx.y, b = blockIdx.z;
-  if (vs_skip(p, b, n)) return;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int last = p.seq - B + t;  // keys 0 .. last exist for this query
-  const float *x = p.x + (((int64_t)b * p.n_heads + n) * B + t) * p.seq;
-  float mx = -INFINITY;
-  for (int s = tid; s <= last; s += 256) mx = fmaxf(mx, x[s]);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-  if (lane == 0) red[w] = mx;
-  __syncthreads();
-  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])) * p.c;
-  __syncthreads();
-  float sum = 0.f;
-  for (int s = tid; s <= last; s += 256) sum += fast_exp2(__builtin_fmaf(x[s], p.c, -mx));
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
-  if (lane == 0) red[w] = sum;
-  __syncthreads();
-  if (tid == 0) {
-    float *st = p.stats + (((int64_t)b * p.n_heads + n) * B + t) * 2;
-    st[0] = mx;
-    st[1] = 1.f / (red[0] + red[1] + red[2] + red[3]);
-  }
-}
-
-// thread i owns key i (vertical sum) and offset i (slash sum); the B queries are added in a fixed order
-template <int B>
-__global__ __launch_bounds__(256) void vs_sums_kernel(VsParams p) {
-  __shared__ float st[B][2];
-  const int n = blockIdx.y, b = blockIdx.z;
-  if (vs_skip(p, b, n)) return;
-  const int64_t hb = (int64_t)b * p.n_heads + n;
-  for (int x = threadIdx.x; x < 2 * B; x += 256) st[x >> 1][x & 1] = p.stats[hb * B * 2 + x];
-  __syncthreads();
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= p.seq) return;
-  const float *x = p.x + hb * B * p.seq;
-  const int t0 = p.seq - B;
-  float av = 0.f, as = 0.f;
-  for (int t = 0; t < B; ++t) {
-    const int tabs = t0 + t;
-    if (i <= tabs) {
-      av += fast_exp2(__builtin_fmaf(x[(int64_t)t * p.seq + i], p.c, -st[t][0])) * st[t][1];
-      as += fast_exp2(__builtin_fmaf(x[(int64_t)t * p.seq + (tabs - i)], p.c, -st[t][0])) * st[t][1];
-    }
-  }
-  p.sums[(hb * 2) * p.seq + i] = av * (1.f / B);
-  p.sums[(hb * 2 + 1) * p.seq + i] = as * (1.f / B);
-}
-
-// Kept keys / offsets -> key-block lists.  flags[b][n][2][nkb] come from the vector selection with rows of
-// `block` entries: bit 0 = a kept entry in the row, bit 1 = a kept entry other than the row's first.  Block
-// (i, j) holds a kept key iff row j of the vertical flags has bit 0; its token pairs realise the offsets
-// (i-j)B - (B-1) .. (i-j)B + (B-1): all of slash row i-j, and slash row i-j-1 without its first entry.
-__global__ __launch_bounds__(256) void vs_block_lists_kernel(VsParams p, const int32_t *__restrict__ flags, int nkb,
-                                                             int forced, int by_head, int32_t *__restrict__ kb_idx,
-                                                             int32_t *__restrict__ kb_cnt) {
-  const int lane = threadIdx.x & 63;
-  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), n = blockIdx.y, b = blockIdx.z;
-  if (i >= nkb || vs_skip(p, b, n)) return;
-  const int head = p.head_ids[n], n_heads = p.n_heads, n_q_heads = p.n_q_heads;
-  const int32_t *fv = flags + (((int64_t)b * n_heads + n) * 2) * nkb, *fs = fv + nkb;
-  // lists are stored per listed position, or per query head when they serve a whole layer
-  const int64_t orow = (by_head ? ((int64_t)b * n_q_heads + head) : ((int64_t)b * n_heads + n)) * nkb + i;
-  int32_t *out = kb_idx + orow * nkb;
-  const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  uint32_t n_out = 0;
-  for (int j0 = 0; j0 <= i; j0 += 64) {
-    const int j = j0 + lane;
-    bool sel = false;
-    if (j <= i) {
-      const int dlt = i - j;
-      sel = (fv[j] & 1) || (fs[dlt] & 1) || (dlt >= 1 && (fs[dlt - 1] & 2)) || (forced && (j == 0 || j == i));
-    }
-    const uint64_t smask = __ballot(sel);
-    if (sel) out[n_out + __popcll(smask & lt)] = j;
-    n_out += __popcll(smask);
-  }
-  for (int pos = n_out + lane; pos < nkb; pos += 64) out[pos] = -1;
-  if (lane == 0) kb_cnt[orow] = (int32_t)n_out;
-}
 
 // ---------------------------------------------------------------------------------------------
 // host side
@@ -2036,81 +542,7 @@ sp_status check_ws(const void *ws, size_t have, size_t need) {
 
 }  // namespace
 
-// ---------------------------------------------------------------------------------------------
-// step-mix probe (measurement aid): the instruction mix of one attention step, nothing around it
-// ---------------------------------------------------------------------------------------------
 namespace {
-
-// Per step and wavefront: G MFMAs on four independent accumulators; a 1 KiB fragment read from LDS for
-// every LP-th MFMA (4 groups ahead of its use, as in attn_kernel); C LDS-direct 1 KiB loads spread over
-// the groups; V FMAs and E exp2 per MFMA; a barrier per step when there are loads.  LDS: a 32 KiB read
-// window, above it the wavefronts' load windows.  Every workgroup streams its own 1 MiB of `src`.
-template <int LP, int C, int V, int E, int G, int LDSB>
-__global__ __launch_bounds__(256) void probe_kernel(const char *__restrict__ src, float *__restrict__ sink, int iters) {
-  static_assert(32768 + 4 * C * 1024 <= LDSB, "load windows must fit");
-  static_assert(G <= 64 && (C == 0 || G % C == 0), "group layout");
-  __shared__ __attribute__((aligned(1024))) char smem[LDSB];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const char *gsrc = src + (size_t)(blockIdx.x % 64) * (1 << 20);
-  for (int i = tid; i < 32768 / 16; i += 256)
-    reinterpret_cast<u32x4 *>(smem)[i] = reinterpret_cast<const u32x4 *>(gsrc)[i];
-  __syncthreads();
-  const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
-  const bf16x8 b = reinterpret_cast<const bf16x8 *>(gsrc + 65536)[tid];
-  f32x16 acc[4];
-#pragma unroll
-  for (int n = 0; n < 4; ++n)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
-  float x[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) x[i] = 0.5f + 0.01f * i + lane * 1e-4f;
-  const char *rd = smem + lane * 16;
-  constexpr int PF = 4;
-  bf16x8 fr[PF + 1];
-#pragma unroll
-  for (int n = 0; n < PF + 1; ++n) fr[n] = b;
-  for (int it = 0; it < iters; ++it) {
-    if (C > 0) {
-      wait_vm<C / 2>();
-      __builtin_amdgcn_s_barrier();
-    }
-    const char *gs = gsrc + (size_t)(it & 7) * 65536 + (size_t)(w * C) * 1024 + 131072;
-    const uint32_t wslot = lds0 + 32768 + (uint32_t)(w * C) * 1024;
-#pragma unroll
-    for (int n = 0; n < G; ++n) {
-      if (LP > 0 && n % LP == 0)
-        fr[(n + PF) % (PF + 1)] = *reinterpret_cast<const bf16x8 *>(rd + (n % 32) * 1024);
-      acc[n % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[LP > 0 ? ((n / LP) * LP) % (PF + 1) : 0], b, acc[n % 4],
-                                                           0, 0, 0);
-#pragma unroll
-      for (int v = 0; v < V; ++v) {
-        const int i = (n * V + v) % 16;
-        x[i] = __builtin_fmaf(x[i], 0.999f, 0.0007f);
-      }
-#pragma unroll
-      for (int e = 0; e < E; ++e) {
-        const float y = fast_exp2(x[(n * E + e + 8) % 16]);
-        asm volatile("" ::"v"(y));
-      }
-      if (C > 0 && n % (G / (C > 0 ? C : 1)) == 1) {
-        constexpr int GAP = G / (C > 0 ? C : 1);
-        lds_dma16(gs + (n / GAP) * 1024, lane * 16, wslot + (n / GAP) * 1024);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
-  wait_vm<0>();
-  float s = 0.f;
-#pragma unroll
-  for (int n = 0; n < 4; ++n)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s += acc[n][r];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) s += x[i];
-  sink[(size_t)blockIdx.x * 256 + tid] = s;
-}
 
 template <int LP, int C, int V, int E, int G, int LDSB>
 sp_status launch_probe(const void *operands, float *sink, int iters, int n_wg, hipStream_t st) {
