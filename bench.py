@@ -343,6 +343,9 @@ def main() -> int:
                     "gate": None if not gate else {"delta": gate[0], "tau": gate[1], "heads_fallen_back": len(fell_back)}},
         "computed_tflops": computed_flops / (ms_step * 1e-3) / 1e12,
         "computed_frac_of_bf16_peak": computed_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        # the same with each diagonal tile counted by its B(B+1)/2 existing pairs instead of as a full tile
+        "computed_tflops_causal_exact": (computed_flops - Hq * nqb * 4.0 * d * (B * (B - 1) / 2.0))
+        / (ms_step * 1e-3) / 1e12,
         "tiles": {"pivot": int(pivot_tiles), "sparse": int(sparse_tiles),
                   "dense_layer": int(Hq * dense_tiles_per_head)},
         "kernel_ms": {kk: (prof[kk][0] / max(prof[kk][1], 1)) for kk in prof},
@@ -354,6 +357,10 @@ def main() -> int:
                      "frac": dense_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.seq is None else None,
                      "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
+                     "traffic_gbs": (MEASURED_TRAFFIC_BYTES[cfg.name] / (dense_avg_ms * 1e-3) / 1e9
+                                     if args.seq is None and cfg.name in MEASURED_TRAFFIC_BYTES and dense_avg_ms > 0
+                                     else None),
+                     "hbm_peak_gbs": PEAK_HBM_GBS,
                      "algorithmic_flops_per_launch": dense_flops_per_launch,
                      "launch_ms": dense_avg_ms},
         "input_gen_s": gen_s,
