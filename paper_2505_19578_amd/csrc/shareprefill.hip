@@ -981,7 +981,7 @@ static sp_status prefill_impl(const sp_shape *shape, const void *q, const void *
     if ((rc = launch_attn<false>(shape, ap, hl, st))) return rc;
   }
   if (hl.n && gated) {
-    // the gate's verdicts live on the device: split the heads there into those that share a list and those
+    // the gate's decisions live on the device: split the heads there into those that share a list and those
     // that fall back to dense, and launch each class on its own, spread evenly over the XCDs
     sort_head_list(hl, Hq / shape->n_kv_heads, false);
     ClassifyParams cp;
