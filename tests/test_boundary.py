@@ -211,3 +211,36 @@ def test_generator_is_deterministic_and_bf16_round_trip():
     q = make_layer(CONFIGS["qwen7b_128k"], seq=512)
     assert sorted(np.bincount(q["head_to_cluster"])) == [4] * 7
     assert all(q["head_to_cluster"][p] == c for c, p in enumerate(q["pivot_heads"]))
+
+
+def test_probe_rejects_bad_arguments_without_launching():
+    import ctypes
+    import paper_2505_19578_amd as sp
+    L = sp.lib()
+    fake = ctypes.c_void_p(4096)     # never dereferenced: validation fails first
+    flops = ctypes.c_double(0.0)
+    ok_ops, ok_sink = sp.SP_PROBE_OPERAND_BYTES, sp.SP_PROBE_SINK_BYTES
+    cases = [
+        (0, None, ok_ops, 10, fake, ok_sink),                    # null operands
+        (0, ctypes.c_void_p(4100), ok_ops, 10, fake, ok_sink),   # operands not 16-byte aligned
+        (0, fake, ok_ops - 1, 10, fake, ok_sink),                # operands too short
+        (0, fake, ok_ops, 10, fake, ok_sink - 1),                # sink too short
+        (len(sp.SP_PROBE_MIXES), fake, ok_ops, 10, fake, ok_sink),
+        (-1, fake, ok_ops, 10, fake, ok_sink),
+        (0, fake, ok_ops, 0, fake, ok_sink),
+        (0, fake, ok_ops, 1000001, fake, ok_sink),
+    ]
+    for mix, ops, nops, iters, sink, nsink in cases:
+        rc = L.sp_probe_step_mix(mix, ops, nops, iters, sink, nsink, ctypes.byref(flops), None)
+        assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG", (mix, nops, iters, nsink)
+    rc = L.sp_probe_step_mix(0, fake, ok_ops, 10, fake, ok_sink, None, None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120)
+    assert res.returncode != 0
+    assert "single-GPU" in res.stderr and res.stdout.strip() == ""
