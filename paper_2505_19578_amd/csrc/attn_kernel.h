@@ -59,7 +59,16 @@ __device__ __forceinline__ float sum_xor32(float x) {
 // harmless in fp32 / bf16, and m, l, the block sums and O stay mutually consistent whatever m is.
 // Moving m only when the max outgrows it by more than the slack makes O rescaling rare (a lane
 // triggers it a handful of times per row instead of at every new maximum).
+// P is rounded to bf16 for the PV product while the row sum l adds the unrounded values.  With m lagging the
+// true max, a row's large weights 2^(x - m) are not exactly representable, so in a row that a few keys
+// dominate numerator and normaliser would differ by those weights' rounding errors (up to 2^-9 of |O|).
+// The kernel therefore keeps a second sum lc = sum of (bf16(p) - p) over every tile that can hold a weight
+// above 1/SP_CARE of the row's running sum (the first tiles of a row, tiles with a sink or a heavy key, and
+// all tiles near the diagonal), and normalises O by l + lc: every weight that matters enters the
+// normaliser as PV saw it; the weights left out are each below 1/SP_CARE of the row, their rounding
+// errors are independent and average out.  The block-mass scores keep using l, so their rows sum to 1.
 constexpr float SP_MAX_SLACK = 8.0f;
+constexpr float SP_CARE = 32.0f;
 __device__ __forceinline__ float lazy_max(float m_ref, float tile_max) {
   return (tile_max > m_ref + SP_MAX_SLACK) ? tile_max : m_ref;
 }
@@ -68,6 +77,23 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 t = {a, b};
   bf16x2 r = __builtin_convertvector(t, bf16x2);
   return __builtin_bit_cast(uint32_t, r);
+}
+
+// sum of the eight bf16 values of a packed P fragment, as fp32
+__device__ __forceinline__ float sum_bf16x8(bf16x8 v) {
+  const u32x4 t = __builtin_bit_cast(u32x4, v);
+  float a = 0.f, b = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    a += __builtin_bit_cast(float, t[e] << 16);
+    b += __builtin_bit_cast(float, t[e] & 0xffff0000u);
+  }
+  return a + b;
+}
+__device__ __forceinline__ float max3f(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
 }
 
 // One wavefront-wide 1 KiB copy HBM/L2 -> LDS without passing through registers: lane l moves the
@@ -170,6 +196,8 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m = -INFINITY, l = 0.f, bs = 0.f;
+  float lc = 0.f;     // sum of bf16(p) - p over the tiles summed twice (see SP_CARE)
+  bool care = true;   // the tile whose max was taken last may hold a weight that matters
 
   int nblk;
   const int32_t *list = nullptr;
@@ -244,6 +272,19 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
         s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ds], s[rb], 0, 0, 0);
       }
   };
+  // move_reference: mx = raw row max of a fresh tile.  Moves the reference if the max outgrew the slack,
+  // rescales the running sums, notes whether the tile's largest weight matters to the row (care), returns
+  // alpha = 2^(m_old - m_new) for the O accumulators.
+  auto move_reference = [&](float mx) -> float {
+    const float m_new = lazy_max(m, mx * p.c);
+    const float alpha = fast_exp2(m - m_new);
+    m = m_new;
+    l *= alpha;
+    bs *= alpha;
+    lc *= alpha;
+    care = fast_exp2(__builtin_fmaf(mx, p.c, -m_new)) * SP_CARE > l;
+    return alpha;
+  };
   // Online softmax, split in two halves that sit in different pipeline steps.
   // tile_max: (optionally causal-masked) row max of a freshly computed S tile; moves the running max,
   // rescales the running sums, returns alpha = 2^(m_old - m_new) for the O accumulators.
@@ -263,12 +304,7 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
 #pragma unroll
       for (int r = (rb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[rb][r], s[rb][r + 1]));
     mx = max_xor32(mx);
-    const float m_new = lazy_max(m, mx * p.c);
-    const float alpha = fast_exp2(m - m_new);
-    m = m_new;
-    l *= alpha;
-    bs *= alpha;
-    return alpha;
+    return move_reference(mx);
   };
   // tile_exp: P = 2^(S*c - m) for a tile whose max is already folded into m; adds the row sums,
   // leaves P rounded to bf16 in pb (the B operand of the PV product)
@@ -291,6 +327,7 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
     const float rs = sum_xor32(rs0 + rs1);
     l += rs;
     bs += rs;
+    lc += sum_xor32(sum_bf16x8(pb[0]) + sum_bf16x8(pb[1]) + sum_bf16x8(pb[2]) + sum_bf16x8(pb[3])) - rs;
   };
   auto rescale = [&](float alpha) {
     if (__any(alpha != 1.f)) {
@@ -351,7 +388,8 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
     bf16x8 fr[PF + 1];
     bf16x8 pb[4];
     u32x4 pt;
-    float rs0 = 0.f, rs1 = 0.f, mx = 0.f, lval = 0.f, alpha = 1.f;
+    float rs0 = 0.f, rs1 = 0.f, mx = 0.f, lval = 0.f, alpha = 1.f, rs_tile = 0.f;
+    const bool care_t = care;  // set when this tile's max was taken
     float xa[16], xb[16];
 #pragma unroll
     for (int n = 0; n < PF; ++n) fr[n] = frag(n);
@@ -391,6 +429,7 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
       }
       if (n == NQ + 2) {
         const float rs = sum_xor32(rs0 + rs1);
+        rs_tile = rs;
         l += rs;
         bs += rs;
         if (SCORES && t % SPB == SPB - 1) {  // end of key block j0: log2 of the block's exp-sum
@@ -412,19 +451,14 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
         for (int u = 0; u < 16; ++u) {
           if (2 + u * (NP - 2 - MAXTAIL) / 16 != np) continue;
           const float a0 = s_next[u / 8][2 * (u % 8)], a1 = s_next[u / 8][2 * (u % 8) + 1];
-          mx = (u == 0) ? fmaxf(a0, a1) : fmaxf(mx, fmaxf(a0, a1));
+          mx = (u == 0) ? fmaxf(a0, a1) : max3f(mx, a0, a1);
         }
-        if (np == NP - MAXTAIL) {
-          mx = max_xor32(mx);
-          const float m_new = lazy_max(m, mx * p.c);
-          alpha = fast_exp2(m - m_new);
-          m = m_new;
-          l *= alpha;
-          bs *= alpha;
-        }
+        if (np == NP - MAXTAIL) alpha = move_reference(max_xor32(mx));
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (__any(care_t))  // rare: the tile summed again as PV saw it (alpha already holds the move after this tile)
+      lc += (sum_xor32(sum_bf16x8(pb[0]) + sum_bf16x8(pb[1]) + sum_bf16x8(pb[2]) + sum_bf16x8(pb[3])) - rs_tile) * alpha;
     rescale(alpha);
     if (SCORES && t % SPB == SPB - 1 && h == 0) lrow[(int64_t)j0 * B] = lval;
   };
@@ -513,7 +547,7 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
 
   // ---- output: O = O^T accumulators / l, rounded to bf16 ----
   {
-    const float inv = (l > 0.f) ? 1.f / l : 0.f;
+    const float inv = (l > 0.f) ? 1.f / (l + lc) : 0.f;
     uint16_t *op = p.o + (int64_t)b * p.o_sb + ((int64_t)i * B + tq) * p.o_st + (int64_t)head * p.o_sh;
 #pragma unroll
     for (int db = 0; db < DB; ++db)

@@ -63,7 +63,7 @@ class LayerConfig:
     sink_boost: float = 4.0    # logit boost of key 0
     heavy_boost: float = 10.0  # logit boost of the heavy vertical keys
     value_gain: float = 4.0    # topic-dependent mean of V (nu)
-    value_noise: float = 0.5   # std of the i.i.d. part of V (keeps |O| < 4, where one bf16 ulp is 2^-6)
+    value_noise: float = 1.0   # std of the i.i.d. part of V (epsilon ~ N(0,1), as the workload statement gives it)
 
     @property
     def cluster_size(self) -> int:
