@@ -170,6 +170,22 @@ sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, 
                                      size_t workspace_bytes, void *hip_stream);
 
 /*
+ * sp_build_block_mask_global for callers that cannot allocate or hand over device memory for scratch
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments,
+ * outputs, errors and results, bit for bit, but no workspace.  The selection's scratch (histograms, tie
+ * counts) lives in a static device array inside the library, SP_STATIC_SCRATCH_BYTES per GPU, held until
+ * the process ends; the call allocates and frees nothing and clears what it needs with a kernel.
+ * Limit: n_maps * (65664 + 8 * nqb rounded up to 256) bytes must fit (e.g. 16 maps at nqb = 1024, 24 at
+ * nqb = 256); larger requests return SP_ERR_UNSUPPORTED and launch nothing.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ * threads) race; calls on one stream, or ordered by events, are safe.
+ */
+#define SP_STATIC_SCRATCH_BYTES ((size_t)2 << 20)
+sp_status sp_build_block_mask_global_static(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb,
+                                            float gamma, int32_t forced, int32_t *kb_idx, int32_t *kb_cnt,
+                                            void *hip_stream);
+
+/*
  * Alg. 3 (Determine Sparse Pattern) for the listed heads.  For each listed head n:
  *   a_hat[n]  = softmax over key blocks of the pooled, scaled logits of the last `block`
  *               queries against every key block (causal inside the last block), i.e. row

@@ -10,7 +10,8 @@ from .binding import (SpError, SpShape, lib, shape_of, sp_workspace_bytes, sp_pr
                       sp_dense_attn_with_block_scores, sp_build_block_mask,
                       sp_block_sparse_attn, sp_prefill_layer, EXPORTED_SYMBOLS,
                       sp_score_workspace_bytes, sp_mask_workspace_bytes, sp_block_mean_logit_scores,
-                      sp_build_block_mask_global, sp_prefill_layer_modes,
+                      sp_build_block_mask_global, sp_build_block_mask_global_static, sp_prefill_layer_modes,
+                      SP_STATIC_SCRATCH_BYTES,
                       sp_determine_pattern, sp_block_sparse_attn_gated, sp_prefill_layer_gated,
                       sp_prefill_layer_dict, pattern_dict_of, SpPatternDict,
                       sp_vs_workspace_bytes, sp_search_vertical_slash, SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH,
@@ -21,7 +22,8 @@ __all__ = ["SpError", "SpShape", "lib", "shape_of", "sp_workspace_bytes", "sp_pr
            "sp_dense_attn_with_block_scores", "sp_build_block_mask",
            "sp_block_sparse_attn", "sp_prefill_layer", "EXPORTED_SYMBOLS",
            "sp_score_workspace_bytes", "sp_mask_workspace_bytes", "sp_block_mean_logit_scores",
-           "sp_build_block_mask_global", "sp_prefill_layer_modes",
+           "sp_build_block_mask_global", "sp_build_block_mask_global_static", "SP_STATIC_SCRATCH_BYTES",
+           "sp_prefill_layer_modes",
            "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated",
            "sp_prefill_layer_dict", "pattern_dict_of", "SpPatternDict",
            "sp_vs_workspace_bytes", "sp_search_vertical_slash", "SP_FALLBACK_DENSE", "SP_FALLBACK_VERTICAL_SLASH",

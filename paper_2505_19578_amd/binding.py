@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "sp_dense_attn_with_block_scores", "sp_build_block_mask",
     "sp_block_sparse_attn", "sp_prefill_layer",
     "sp_score_workspace_bytes", "sp_mask_workspace_bytes", "sp_block_mean_logit_scores",
-    "sp_build_block_mask_global", "sp_prefill_layer_modes",
+    "sp_build_block_mask_global", "sp_build_block_mask_global_static", "sp_prefill_layer_modes",
     "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated", "sp_prefill_layer_dict",
     "sp_vs_workspace_bytes", "sp_search_vertical_slash", "sp_probe_step_mix",
 ]
@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = [
 SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH = 0, 1
 SP_PROBE_MIXES = ("mfma", "lds_read", "ring", "step", "step_64q")  # index = the header's SP_PROBE_* value
 SP_PROBE_OPERAND_BYTES, SP_PROBE_SINK_BYTES = 64 << 20, 4 << 20
+SP_STATIC_SCRATCH_BYTES = 2 << 20
 
 SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT = 0, 1
 SP_SELECT_PER_ROW, SP_SELECT_GLOBAL = 0, 1
@@ -97,6 +98,9 @@ def lib() -> ctypes.CDLL:
         L.sp_build_block_mask_global.restype = ctypes.c_int
         L.sp_build_block_mask_global.argtypes = [fp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                                  ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.sp_build_block_mask_global_static.restype = ctypes.c_int
+        L.sp_build_block_mask_global_static.argtypes = [fp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                        ctypes.c_float, ctypes.c_int32, vp, vp, vp]
         L.sp_prefill_layer_modes.restype = ctypes.c_int
         L.sp_prefill_layer_modes.argtypes = [sp, vp, vp, vp, ip, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_int32,
                                              ctypes.c_int32, vp, fp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -238,6 +242,12 @@ def sp_build_block_mask_global(block_scores, n_maps: int, nqb: int, nkb: int, ga
     _check(lib().sp_build_block_mask_global(_ptr(block_scores), n_maps, nqb, nkb, ctypes.c_float(gamma),
                                             1 if forced else 0, _ptr(kb_idx), _ptr(kb_cnt), _ptr(workspace),
                                             _nbytes(workspace), _stream()))
+
+
+def sp_build_block_mask_global_static(block_scores, n_maps: int, nqb: int, nkb: int, gamma: float, forced: bool,
+                                      kb_idx, kb_cnt):
+    _check(lib().sp_build_block_mask_global_static(_ptr(block_scores), n_maps, nqb, nkb, ctypes.c_float(gamma),
+                                                   1 if forced else 0, _ptr(kb_idx), _ptr(kb_cnt), _stream()))
 
 
 def sp_prefill_layer_modes(shape: SpShape, q, k, v, head_to_cluster, pivot_heads, gamma: float, score_mode: int,

@@ -35,6 +35,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "shareprefill.h"
@@ -542,6 +543,43 @@ sp_status check_ws(const void *ws, size_t have, size_t need) {
 
 }  // namespace
 
+// Device memory of the one entry point that takes no workspace (sp_build_block_mask_global_static): a
+// file-scope array, one copy per GPU the library runs on, held until the process ends.  The array's name
+// is only a host-side handle; its device address is looked up once per device and every launch gets that
+// pointer.
+static __device__ __align__(256) char scratch[SP_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int SP_MAX_DEVICES = 64;
+char *g_static_scratch[SP_MAX_DEVICES] = {nullptr};
+std::mutex g_static_scratch_mutex;
+
+// device address of `scratch` on the current device (no allocation: a symbol lookup, cached per device)
+sp_status static_scratch_ptr(char **out) {
+  int dev = -1;
+  sp_status rc = hip_check(hipGetDevice(&dev), "hipGetDevice");
+  if (rc) return rc;
+  if (dev < 0 || dev >= SP_MAX_DEVICES) {
+    set_err("device ordinal %d outside [0, %d)", dev, SP_MAX_DEVICES);
+    return SP_ERR_UNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+  if (!g_static_scratch[dev]) {
+    void *ptr = nullptr;
+    if ((rc = hip_check(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)"))) return rc;
+    if (!ptr || ((uintptr_t)ptr % 256)) {
+      set_err("static scratch address %p is null or misaligned", ptr);
+      return SP_ERR_HIP;
+    }
+    g_static_scratch[dev] = (char *)ptr;
+  }
+  *out = g_static_scratch[dev];
+  return SP_OK;
+}
+
+}  // namespace
+
 namespace {
 
 template <int LP, int C, int V, int E, int G, int LDSB>
@@ -823,10 +861,8 @@ sp_status sp_block_mean_logit_scores(const sp_shape *shape, const void *q, const
                                   (hipStream_t)hip_stream);
 }
 
-sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb, float gamma,
-                                     int32_t forced, int32_t *kb_idx, int32_t *kb_cnt, void *workspace,
-                                     size_t workspace_bytes, void *hip_stream) {
-  g_err[0] = 0;
+static sp_status check_mask_global_args(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb, float gamma,
+                                        const int32_t *kb_idx, const int32_t *kb_cnt) {
   if (!block_scores || !kb_idx || !kb_cnt) {
     set_err("block_scores / kb_idx / kb_cnt must not be NULL");
     return SP_ERR_INVALID_ARG;
@@ -847,9 +883,35 @@ sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, 
     set_err("gamma %g outside (0, 1]", (double)gamma);
     return SP_ERR_INVALID_ARG;
   }
-  sp_status rc = check_ws(workspace, workspace_bytes, align_up((size_t)n_maps * gsel_map_bytes(nqb), 256));
+  return SP_OK;
+}
+
+sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb, float gamma,
+                                     int32_t forced, int32_t *kb_idx, int32_t *kb_cnt, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_mask_global_args(block_scores, n_maps, nqb, nkb, gamma, kb_idx, kb_cnt);
   if (rc) return rc;
+  if ((rc = check_ws(workspace, workspace_bytes, align_up((size_t)n_maps * gsel_map_bytes(nqb), 256)))) return rc;
   return launch_mask_global(block_scores, n_maps, nqb, gamma, forced != 0, kb_idx, kb_cnt, (char *)workspace,
+                            (hipStream_t)hip_stream);
+}
+
+sp_status sp_build_block_mask_global_static(const float *block_scores, int32_t n_maps, int32_t nqb, int32_t nkb,
+                                            float gamma, int32_t forced, int32_t *kb_idx, int32_t *kb_cnt,
+                                            void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_mask_global_args(block_scores, n_maps, nqb, nkb, gamma, kb_idx, kb_cnt);
+  if (rc) return rc;
+  const size_t need = align_up((size_t)n_maps * gsel_map_bytes(nqb), 256);
+  if (need > SP_STATIC_SCRATCH_BYTES) {
+    set_err("selection scratch of %zu bytes (n_maps %d, nqb %d) exceeds the library's static %zu bytes; "
+            "use sp_build_block_mask_global with a workspace", need, n_maps, nqb, (size_t)SP_STATIC_SCRATCH_BYTES);
+    return SP_ERR_UNSUPPORTED;
+  }
+  char *scratch_dev = nullptr;
+  if ((rc = static_scratch_ptr(&scratch_dev))) return rc;
+  return launch_mask_global(block_scores, n_maps, nqb, gamma, forced != 0, kb_idx, kb_cnt, scratch_dev,
                             (hipStream_t)hip_stream);
 }
 
