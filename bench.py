@@ -28,10 +28,25 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
-# HBM/fabric bytes per launch of the dense-pivot kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# passes summarised in profiles/prefill_layer_llama8b_128k.md (counters scaled by a 1 GiB copy; a
-# benchmark run cannot collect counters itself, so the figure is carried here per workload)
-MEASURED_TRAFFIC_BYTES = {"llama8b_128k": 14.01e9}
+# HBM/fabric bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes (counters scaled by a
+# 1 GiB copy).  A benchmark run cannot collect counters itself, so the figures are carried here per workload and
+# kernel together with the profile summary they come from and the digest of the kernel sources that summary was
+# made with (kernel_source_digest() below); a run whose sources differ reports null.
+MEASURED_TRAFFIC = {
+    "llama8b_128k": {"profile": "profiles/prefill_layer_llama8b_128k.md", "source_digest": "unset",
+                     "dense_bytes": 14.01e9, "sparse_bytes": 46.07e9},
+}
+
+
+def kernel_source_digest() -> str:
+    """sha256 (first 16 hex digits) over the library's sources: names the build a counter figure belongs to."""
+    import hashlib
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_2505_19578_amd", "csrc")
+    for name in sorted(os.listdir(src)) + ["../../include/shareprefill.h"]:
+        with open(os.path.join(src, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
 
 
 def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
@@ -76,13 +91,15 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    sp.sp_profile_enable(True)
-    sp.sp_profile_read(reset=True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    sp.sp_profile_enable(True)          # per-kernel durations from a second, separately bracketed pass
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
     prof = sp.sp_profile_read(reset=True)
     sp.sp_profile_enable(False)
     ms_step = wall * 1e3 / args.steps
@@ -129,40 +146,6 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
     return 0
 
 
-def bench_mix_probe(args, sp, torch) -> int:
-    """What the machine sustains for the instruction mix of one attention step, on operand data like the
-    workload's (standard-normal bf16) and on zeros: the matrix-pipe clock of the part depends on the data."""
-    n16 = sp.SP_PROBE_OPERAND_BYTES // 2
-    g = torch.Generator(device="cuda")
-    g.manual_seed(20250519)
-    data = {"normal": torch.randn(n16, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16),
-            "zeros": torch.zeros(n16, device="cuda", dtype=torch.bfloat16)}
-    sink = torch.empty(sp.SP_PROBE_SINK_BYTES // 4, dtype=torch.float32, device="cuda")
-    iters, out = 40000, {}
-    for kind, operands in data.items():
-        for mix, name in enumerate(sp.SP_PROBE_MIXES):
-            n_it = iters // (2 if name == "step_64q" else 1)      # 64 MFMAs per step instead of 32
-            for _ in range(max(args.warmup, 1)):
-                flops = sp.sp_probe_step_mix(mix, operands, n_it, sink)
-            marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-            marks[0].record()
-            for n in range(args.steps):
-                sp.sp_probe_step_mix(mix, operands, n_it, sink)
-                marks[n + 1].record()
-            torch.cuda.synchronize()
-            ms = sorted(marks[n].elapsed_time(marks[n + 1]) for n in range(args.steps))
-            tf = flops / (ms[len(ms) // 2] * 1e-3) / 1e12
-            out[f"{kind}/{name}"] = {"ms_median": round(ms[len(ms) // 2], 3), "tflops": round(tf, 1),
-                                     "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
-            print(f"mix-probe {kind:7s} {name:9s} {ms[len(ms) // 2]:8.2f} ms  {tf:7.1f} TFLOP/s  "
-                  f"{tf / PEAK_BF16_TFLOPS:.3f} of peak", file=sys.stderr, flush=True)
-    print(json.dumps({"metric": "step-mix probe: matrix TFLOP/s sustained by the instruction mix of one attention step",
-                      "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
-                      "peak": PEAK_BF16_TFLOPS, "data": "synthetic (standard-normal bf16 operands, and zeros)",
-                      "mixes": out}))
-    return 0
-
-
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,9 +167,6 @@ def main() -> int:
                     help="with --dict-layers: what heads that fail Alg. 3 run (dense, or the vertical-slash pattern of Alg. 5)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into a HIP graph and time replays (the calls enqueue kernels only)")
-    ap.add_argument("--mix-probe", action="store_true",
-                    help="instead of the layer: time the library's step-mix probe (the instruction mix of one "
-                         "attention step on normal and on zero operand data), one JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-all", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -203,8 +183,6 @@ def main() -> int:
     from synth import CONFIGS, make_layer
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    if args.mix_probe:
-        return bench_mix_probe(args, sp, torch)
     if args.dict_layers > 0:
         return bench_dict(args, sp, torch, np, CONFIGS, make_layer)
     t0 = time.time()
@@ -267,8 +245,7 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    sp.sp_profile_enable(True)
-    sp.sp_profile_read(reset=True)
+    # timed region: exactly `steps` steps, nothing else on the stream (no per-kernel events)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # same stream as the launches
     t0 = time.perf_counter()
     marks[0].record()
@@ -278,9 +255,19 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     per_step = sorted(marks[n].elapsed_time(marks[n + 1]) for n in range(args.steps))
-    prof = sp.sp_profile_read(reset=True)
-    sp.sp_profile_enable(False)
     ms_step = wall * 1e3 / args.steps
+    # a second pass of the same steps with every kernel bracketed by HIP events on the launch stream:
+    # the per-kernel durations behind the roofline objects (not part of ms_per_step)
+    prof = None
+    if not args.graph:
+        sp.sp_profile_enable(True)
+        for n in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        prof = sp.sp_profile_read(reset=True)
+        sp.sp_profile_enable(False)
+    if prof is None:
+        prof = {kk: (0.0, 0) for kk in ("pack", "dense", "mask", "sparse", "score", "vs")}
 
     # work actually done
     cnt = kb_cnt.cpu().numpy()[0].astype(np.int64)            # [C][nqb]
@@ -309,7 +296,9 @@ def main() -> int:
     dense_tflops = dense_flops_per_launch / (dense_avg_ms * 1e-3) / 1e12 if dense_avg_ms > 0 else 0.0
     sparse_ms, sparse_n = prof["sparse"]
     sparse_avg_ms = sparse_ms / max(sparse_n, 1)
-    sparse_tflops = sparse_tiles * tile_flops / (sparse_avg_ms * 1e-3) / 1e12 if sparse_avg_ms > 0 else 0.0
+    sparse_per_step = max(sparse_n // max(args.steps, 1), 1)     # sparse launches per step (2 with the gate)
+    sparse_tflops = (sparse_tiles * tile_flops / sparse_per_step / (sparse_avg_ms * 1e-3) / 1e12
+                     if sparse_avg_ms > 0 else 0.0)
 
     # the "vs dense" denominator: this library's own dense kernel on every head, no scores
     dense_all_ms = None
@@ -317,13 +306,24 @@ def main() -> int:
         heads = list(range(Hq))
         sp.sp_dense_attn_with_block_scores(shape, q, k, v, heads, o, None, ws)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        reps = 2
-        for _ in range(reps):
+        reps = 5
+        dm = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        dm[0].record()
+        for n in range(reps):
             sp.sp_dense_attn_with_block_scores(shape, q, k, v, heads, o, None, ws)
+            dm[n + 1].record()
         torch.cuda.synchronize()
-        dense_all_ms = (time.perf_counter() - t0) * 1e3 / reps
+        dense_all_ms = dm[0].elapsed_time(dm[reps]) / reps
 
+    # counter figures carried from a profile: only for the workload and the build they were taken on
+    digest = kernel_source_digest()
+    rec = MEASURED_TRAFFIC.get(cfg.name) if (args.seq is None and default_modes and not gate) else None
+    traffic, traffic_source = {}, None
+    if rec is not None:
+        traffic_source = {"profile": rec["profile"], "source_digest": rec["source_digest"],
+                          "matches_this_build": rec["source_digest"] == digest}
+        if rec["source_digest"] == digest:
+            traffic = rec
     out = {
         "metric": "sparse-prefill attention ms/layer at 128K + effective TFLOP/s vs dense",
         "value": dense_equiv_flops / (ms_step * 1e-3) / 1e12,
@@ -355,14 +355,26 @@ def main() -> int:
         "roofline": {"kernel": "attn_kernel<dense> (pivot heads + block scores)", "bound": "mfma",
                      "achieved": dense_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": dense_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.seq is None else None,
+                     "traffic": traffic.get("dense_bytes"),
                      "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
-                     "traffic_gbs": (MEASURED_TRAFFIC_BYTES[cfg.name] / (dense_avg_ms * 1e-3) / 1e9
-                                     if args.seq is None and cfg.name in MEASURED_TRAFFIC_BYTES and dense_avg_ms > 0
-                                     else None),
+                     "traffic_source": traffic_source,
+                     "traffic_gbs": (traffic["dense_bytes"] / (dense_avg_ms * 1e-3) / 1e9
+                                     if traffic.get("dense_bytes") and dense_avg_ms > 0 else None),
                      "hbm_peak_gbs": PEAK_HBM_GBS,
                      "algorithmic_flops_per_launch": dense_flops_per_launch,
-                     "launch_ms": dense_avg_ms},
+                     "launch_ms": dense_avg_ms, "launches_timed": dense_n},
+        "roofline_sparse": {"kernel": "attn_kernel<block-sparse> (heads sharing their cluster's lists)", "bound": "mfma",
+                            "achieved": sparse_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                            "frac": sparse_tflops / PEAK_BF16_TFLOPS,
+                            "traffic": traffic.get("sparse_bytes"),
+                            "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled)",
+                            "traffic_source": traffic_source,
+                            "traffic_gbs": (traffic["sparse_bytes"] / (sparse_avg_ms * 1e-3) / 1e9
+                                            if traffic.get("sparse_bytes") and sparse_avg_ms > 0 else None),
+                            "algorithmic_flops_per_launch": sparse_tiles * tile_flops / sparse_per_step,
+                            "tiles_from_kb_cnt": int(sparse_tiles),
+                            "launch_ms": sparse_avg_ms, "launches_timed": sparse_n},
+        "kernel_source_digest": digest,
         "input_gen_s": gen_s,
     }
     # the published peak next to what this board's CU count and maximum engine clock give

@@ -24,8 +24,10 @@
  *     token and head; head_dim is contiguous; every row start must be 16-byte
  *     aligned (strides multiples of 8 elements).
  *   - Supported envelope: head_dim in {64,128}, block in {64,128},
- *     seq % 128 == 0, seq / block <= 32768, n_q_heads % n_kv_heads == 0.
- *     Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *     seq % block == 0, seq / block <= 32768 (an index limit: the workspace of a call that
+ *     produces block-mass score maps grows as 2 * seq * (seq / block + 1) bytes per scored head,
+ *     2.1 GB per head at seq 131072 / block 128, so memory binds long before it),
+ *     n_q_heads % n_kv_heads == 0.  Query head h reads KV head h / (n_q_heads / n_kv_heads).
  */
 #ifndef SHAREPREFILL_H
 #define SHAREPREFILL_H
@@ -65,7 +67,9 @@ const char *sp_last_error(void);
  * kernel kind into host arrays ms[6] / launches[6]: 0 = K/V packing, 1 = dense attention
  * (+ block-mass scores), 2 = mask builder, 3 = block-sparse attention, 4 = block-mean-logit
  * scores and the Alg. 3 gate, 5 = vertical-slash search; `reset` != 0 drops the records.
- * Process-wide and not thread-safe.
+ * sp_profile_enable(1) creates a fixed pool of events (4096 launches between two reads; more are
+ * reported as SP_ERR_UNSUPPORTED by the next read) and clears the records; nothing is created or
+ * freed while launches are enqueued.  Process-wide; do not enable it under HIP graph capture.
  */
 sp_status sp_profile_enable(int32_t on);
 sp_status sp_profile_read(float *ms, int32_t *launches, int32_t reset);
@@ -175,7 +179,7 @@ sp_status sp_build_block_mask_global(const float *block_scores, int32_t n_maps, 
  * outputs, errors and results, bit for bit, but no workspace.  The selection's scratch (histograms, tie
  * counts) lives in a static device array inside the library, SP_STATIC_SCRATCH_BYTES per GPU, held until
  * the process ends; the call allocates and frees nothing and clears what it needs with a kernel.
- * Limit: n_maps * (65664 + 8 * nqb rounded up to 256) bytes must fit (e.g. 16 maps at nqb = 1024, 24 at
+ * Limit: n_maps * (65664 + 8 * nqb rounded up to 256) bytes must fit (e.g. 28 maps at nqb = 1024, 31 at
  * nqb = 256); larger requests return SP_ERR_UNSUPPORTED and launch nothing.
  * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
  * threads) race; calls on one stream, or ordered by events, are safe.
@@ -237,9 +241,10 @@ enum { SP_SELECT_PER_ROW = 0,     /* sp_build_block_mask */
  *   head_to_cluster host [n_q_heads]  cluster id in [0,n_clusters) or -1 (runs dense)
  *   pivot_heads     host [n_clusters] pivot_heads[c] must lie in cluster c
  *   o               device bf16, every head written
- *   block_scores    device fp32 [batch][n_clusters][nqb][nkb]   (required, output)
+ *   block_scores    device fp32 [batch][n_clusters][nqb][nkb] (output), or NULL: the maps then
+ *                   live in the workspace only and are not returned
  *   kb_idx, kb_cnt  device int32 [batch][n_clusters][nqb][nkb] / [..][nqb] (required, output)
- *   workspace       sized by sp_workspace_bytes(shape, n_clusters, ..)
+ *   workspace       sized by sp_workspace_bytes(shape, n_clusters)
  */
 sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
                            const int32_t *head_to_cluster, const int32_t *pivot_heads, int32_t n_clusters,
@@ -353,40 +358,6 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
                                 const sp_pattern_dict *dict, void *o, float *block_scores, int32_t *role, float *a_hat,
                                 float *dist, int32_t *vs_idx, int32_t *vs_cnt, void *workspace, size_t workspace_bytes,
                                 void *hip_stream);
-
-/*
- * Measurement aid, not a step of the method: the instruction mix of one attention step of the
- * kernels above with nothing around it, so that the rate the attention kernels reach can be read
- * against what this machine sustains for the same mix on the same kind of operand data (the
- * matrix-pipe rate of the part depends on the operand values: it lowers its clock under the
- * switching power of random data).  Every wavefront of a grid that fills the device runs
- * `iters` steps; a step is 32 (mix 4: 64) v_mfma_f32_32x32x16_bf16 plus, depending on `mix`,
- *   SP_PROBE_MFMA      nothing else
- *   SP_PROBE_LDS_READ  + one 1 KiB LDS fragment read per MFMA (the streamed K / V operand)
- *   SP_PROBE_RING      + 8 LDS-direct 1 KiB loads per wavefront and step and one barrier per step
- *   SP_PROBE_STEP      + 4 fp32 FMAs and one exp2 per MFMA (the softmax's share): this library's step
- *   SP_PROBE_STEP_64Q  the same work per MFMA for 64 queries per wavefront: 64 MFMAs per step, a fragment
- *                      read every second MFMA, the same 8 LDS-direct loads per step, one wavefront per SIMD
- *   operands    device, bf16 values the matrix pipe is fed with, at least SP_PROBE_OPERAND_BYTES,
- *               16-byte aligned; read only
- *   iters       1 .. 1000000
- *   sink        device fp32, at least SP_PROBE_SINK_BYTES; receives one value per lane (ignored data)
- *   mfma_flops  host, output: matrix flops of the launch (2*32*32*16 per MFMA and wavefront)
- * The call only enqueues the kernel on hip_stream; the caller times it (HIP events on that stream).
- * Returns SP_ERR_INVALID_ARG for a null pointer, a misaligned or short buffer, an unknown mix or
- * iters out of range.
- */
-enum {
-  SP_PROBE_MFMA = 0,
-  SP_PROBE_LDS_READ = 1,
-  SP_PROBE_RING = 2,
-  SP_PROBE_STEP = 3,
-  SP_PROBE_STEP_64Q = 4
-};
-#define SP_PROBE_OPERAND_BYTES ((size_t)64 << 20)
-#define SP_PROBE_SINK_BYTES ((size_t)4 << 20)
-sp_status sp_probe_step_mix(int32_t mix, const void *operands, size_t operand_bytes, int32_t iters, float *sink,
-                            size_t sink_bytes, double *mfma_flops, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ from .binding import (SpError, SpShape, lib, shape_of, sp_workspace_bytes, sp_pr
                       sp_prefill_layer_dict, pattern_dict_of, SpPatternDict,
                       sp_vs_workspace_bytes, sp_search_vertical_slash, SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH,
                       SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT, SP_SELECT_PER_ROW, SP_SELECT_GLOBAL,
-                      sp_probe_step_mix, SP_PROBE_MIXES, SP_PROBE_OPERAND_BYTES, SP_PROBE_SINK_BYTES)
+                      )
 
 __all__ = ["SpError", "SpShape", "lib", "shape_of", "sp_workspace_bytes", "sp_profile_enable", "sp_profile_read",
            "sp_dense_attn_with_block_scores", "sp_build_block_mask",
@@ -28,4 +28,4 @@ __all__ = ["SpError", "SpShape", "lib", "shape_of", "sp_workspace_bytes", "sp_pr
            "sp_prefill_layer_dict", "pattern_dict_of", "SpPatternDict",
            "sp_vs_workspace_bytes", "sp_search_vertical_slash", "SP_FALLBACK_DENSE", "SP_FALLBACK_VERTICAL_SLASH",
            "SP_SCORE_BLOCK_MASS", "SP_SCORE_MEAN_LOGIT", "SP_SELECT_PER_ROW", "SP_SELECT_GLOBAL",
-           "sp_probe_step_mix", "SP_PROBE_MIXES", "SP_PROBE_OPERAND_BYTES", "SP_PROBE_SINK_BYTES"]
+           ]

@@ -18,12 +18,10 @@ EXPORTED_SYMBOLS = [
     "sp_score_workspace_bytes", "sp_mask_workspace_bytes", "sp_block_mean_logit_scores",
     "sp_build_block_mask_global", "sp_build_block_mask_global_static", "sp_prefill_layer_modes",
     "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated", "sp_prefill_layer_dict",
-    "sp_vs_workspace_bytes", "sp_search_vertical_slash", "sp_probe_step_mix",
+    "sp_vs_workspace_bytes", "sp_search_vertical_slash",
 ]
 
 SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH = 0, 1
-SP_PROBE_MIXES = ("mfma", "lds_read", "ring", "step", "step_64q")  # index = the header's SP_PROBE_* value
-SP_PROBE_OPERAND_BYTES, SP_PROBE_SINK_BYTES = 64 << 20, 4 << 20
 SP_STATIC_SCRATCH_BYTES = 2 << 20
 
 SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT = 0, 1
@@ -124,9 +122,6 @@ def lib() -> ctypes.CDLL:
         L.sp_search_vertical_slash.restype = ctypes.c_int
         L.sp_search_vertical_slash.argtypes = [sp, vp, vp, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_int32, fp, vp,
                                                vp, vp, ctypes.c_size_t, vp]
-        L.sp_probe_step_mix.restype = ctypes.c_int
-        L.sp_probe_step_mix.argtypes = [ctypes.c_int32, vp, ctypes.c_size_t, ctypes.c_int32, fp, ctypes.c_size_t,
-                                        ctypes.POINTER(ctypes.c_double), vp]
         _lib = L
     return _lib
 
@@ -314,11 +309,3 @@ def sp_search_vertical_slash(shape: SpShape, q, k, head_ids, gamma: float, force
     _check(lib().sp_search_vertical_slash(
         ctypes.byref(shape), _ptr(q), _ptr(k), _ids(head_ids), len(head_ids), ctypes.c_float(gamma),
         1 if forced else 0, _ptr(sums), _ptr(kb_idx), _ptr(kb_cnt), _ptr(workspace), _nbytes(workspace), _stream()))
-
-
-def sp_probe_step_mix(mix: int, operands, iters: int, sink) -> float:
-    """Enqueue one launch of the step-mix probe on the current stream; returns its matrix flops."""
-    flops = ctypes.c_double(0.0)
-    _check(lib().sp_probe_step_mix(mix, _ptr(operands), _nbytes(operands), iters, _ptr(sink), _nbytes(sink),
-                                   ctypes.byref(flops), _stream()))
-    return flops.value

@@ -17,7 +17,7 @@ struct AttnParams {
   int seq, nqb, n_kv_heads, group, n_heads, n_maps;
   int rgroups;  // ceil(nqb / 8): query-block rows per strand (see the workgroup mapping in attn_kernel)
   float c;    // softmax scale * log2(e)
-  float *lws;     // dense: block-local log2-sum-exp [b][n][nqb][nkb][B], or null
+  float *lws;     // dense: block-local log2-sum-exp [b][n][nqb(nqb+1)/2][B] (row i, key block j <= i), or null
   float *scores;  // dense: [b][n][nqb][nkb], or null
   const int32_t *kb_idx;  // sparse: [b][n_maps][nqb][nkb]
   const int32_t *kb_cnt;  // sparse: [b][n_maps][nqb]
@@ -227,7 +227,9 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
   const int nsub = nblk * SPB;
   const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
   float *lrow = nullptr;
-  if (SCORES) lrow = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb) * B + tq;
+  // block log-sum-exps: causal half, row i of a (batch entry, head) starts at i(i+1)/2 key-block slots
+  const int64_t lws_row = ((int64_t)b * p.n_heads + hpos) * ((int64_t)p.nqb * (p.nqb + 1) / 2) + (int64_t)i * (i + 1) / 2;
+  if (SCORES) lrow = p.lws + lws_row * B + tq;
 
   // key block of sub-tile t (t clamped to the sequence; list entries clamped into [0, i]: memory-safe
   // whatever the list holds)
@@ -579,7 +581,7 @@ __global__ __launch_bounds__(B * 2, B / 64) void attn_kernel(AttnParams p) {
     float lt[TPL];
 #pragma unroll
     for (int tt = 0; tt < TPL; ++tt) lt[tt] = lse_sh[lane + 64 * tt];
-    const float *lblk = p.lws + ((((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb) * B;
+    const float *lblk = p.lws + lws_row * B;
     float *srow = p.scores + (((int64_t)b * p.n_heads + hpos) * p.nqb + i) * nkb;
     const int jr = lane % JB, jp = lane / JB;
     for (int j0 = w * JB; j0 <= i; j0 += NW * JB) {

@@ -47,7 +47,6 @@
 #include "pattern_kernels.h"
 #include "global_select_kernels.h"
 #include "vertical_slash_kernels.h"
-#include "probe_kernel.h"
 
 namespace {
 
@@ -77,8 +76,8 @@ sp_status check_shape(const sp_shape *s) {
     set_err("block %d unsupported (64 or 128)", s->block);
     return SP_ERR_UNSUPPORTED;
   }
-  if (s->seq % 128) {
-    set_err("seq %d is not a multiple of 128", s->seq);
+  if (s->seq % s->block) {
+    set_err("seq %d is not a multiple of block %d", s->seq, s->block);
     return SP_ERR_UNSUPPORTED;
   }
   if (s->seq / s->block > 32768) {
@@ -112,9 +111,15 @@ sp_status check_shape(const sp_shape *s) {
 size_t pack_bytes(const sp_shape *s) {
   return align_up((size_t)s->batch * s->n_kv_heads * s->seq * s->head_dim * 2 * 2, 256);
 }
+// block log-sum-exps of the scored heads: one float per (query, key block <= query block), i.e. the causal
+// half [nqb(nqb+1)/2][block] per (batch entry, head)
 size_t lws_bytes(const sp_shape *s, int n_dense) {
   const size_t nqb = s->seq / s->block;
-  return align_up((size_t)s->batch * n_dense * nqb * nqb * s->block * sizeof(float), 256);
+  return align_up((size_t)s->batch * n_dense * (nqb * (nqb + 1) / 2) * s->block * sizeof(float), 256);
+}
+size_t scores_bytes(const sp_shape *s, int n_maps) {
+  const size_t nqb = s->seq / s->block;
+  return align_up((size_t)s->batch * n_maps * nqb * nqb * sizeof(float), 256);
 }
 
 // scratch of the pooled score path for n listed heads per batch entry and of the global selection
@@ -444,7 +449,7 @@ sp_status launch_vertical_slash(const sp_shape *s, const void *q, const void *k,
   for (int a = 0; a < n; ++a) vp.head_ids[a] = heads[a];
   int32_t *flags = (int32_t *)(vs_ws + L.flags);
   ProfScope prof(KK_VS, st);
-  const dim3 glog(s->seq / 128, n, s->batch), gstat(s->block, n, s->batch), gsum((s->seq + 255) / 256, n, s->batch);
+  const dim3 glog((s->seq + 127) / 128, n, s->batch), gstat(s->block, n, s->batch), gsum((s->seq + 255) / 256, n, s->batch);
 #define SP_VS(D_, B_)                                                                  \
   do {                                                                                 \
     hipLaunchKernelGGL((vs_logits_kernel<D_, B_>), glog, dim3(256), 0, st, vp);        \
@@ -580,17 +585,6 @@ sp_status static_scratch_ptr(char **out) {
 
 }  // namespace
 
-namespace {
-
-template <int LP, int C, int V, int E, int G, int LDSB>
-sp_status launch_probe(const void *operands, float *sink, int iters, int n_wg, hipStream_t st) {
-  hipLaunchKernelGGL((probe_kernel<LP, C, V, E, G, LDSB>), dim3(n_wg), dim3(256), 0, st, (const char *)operands, sink,
-                     iters);
-  return hip_check(hipGetLastError(), "probe_kernel launch");
-}
-
-}  // namespace
-
 extern "C" {
 
 const char *sp_status_string(sp_status s) {
@@ -608,6 +602,22 @@ const char *sp_last_error(void) { return g_err; }
 
 
 sp_status sp_profile_enable(int32_t on) {
+  g_err[0] = 0;
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  if (on && !g_prof_events) {  // the events are created here, never while launches are being enqueued
+    g_prof_events = new hipEvent_t[2 * SP_PROF_CAPACITY];
+    for (int a = 0; a < 2 * SP_PROF_CAPACITY; ++a) {
+      const hipError_t e = hipEventCreate(&g_prof_events[a]);
+      if (e != hipSuccess) {
+        for (int c = 0; c < a; ++c) (void)hipEventDestroy(g_prof_events[c]);
+        delete[] g_prof_events;
+        g_prof_events = nullptr;
+        return hip_check(e, "hipEventCreate");
+      }
+    }
+  }
+  g_prof_count = 0;
+  g_prof_dropped = 0;
   g_prof_on = on != 0;
   return SP_OK;
 }
@@ -618,29 +628,24 @@ sp_status sp_profile_read(float *ms, int32_t *launches, int32_t reset) {
     set_err("ms / launches must not be NULL");
     return SP_ERR_INVALID_ARG;
   }
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
   for (int a = 0; a < KK_COUNT; ++a) {
     ms[a] = 0.f;
     launches[a] = 0;
   }
-  sp_status rc = SP_OK;
-  for (const ProfRec &r : g_prof) {
+  if (g_prof_dropped) {
+    set_err("%d launches were not timed: more than %d launches between two reads", g_prof_dropped, SP_PROF_CAPACITY);
+    return SP_ERR_UNSUPPORTED;
+  }
+  for (int r = 0; r < g_prof_count; ++r) {
     float t = 0.f;
-    const hipError_t e = hipEventElapsedTime(&t, r.e0, r.e1);
-    if (e != hipSuccess) {
-      rc = hip_check(e, "hipEventElapsedTime (synchronise the stream before sp_profile_read)");
-      break;
-    }
-    ms[r.kind] += t;
-    launches[r.kind] += 1;
+    const hipError_t e = hipEventElapsedTime(&t, g_prof_events[2 * r], g_prof_events[2 * r + 1]);
+    if (e != hipSuccess) return hip_check(e, "hipEventElapsedTime (synchronise the stream before sp_profile_read)");
+    ms[g_prof_kind[r]] += t;
+    launches[g_prof_kind[r]] += 1;
   }
-  if (reset && rc == SP_OK) {
-    for (const ProfRec &r : g_prof) {
-      (void)hipEventDestroy(r.e0);
-      (void)hipEventDestroy(r.e1);
-    }
-    g_prof.clear();
-  }
-  return rc;
+  if (reset) g_prof_count = 0;
+  return SP_OK;
 }
 
 sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_t *bytes) {
@@ -657,7 +662,8 @@ sp_status sp_workspace_bytes(const sp_shape *shape, int32_t n_dense_heads, size_
   }
   *bytes = pack_bytes(shape) + lws_bytes(shape, n_dense_heads) +
            std::max(pattern_layout(shape, n_dense_heads).total, pattern_layout(shape, shape->n_q_heads).total) +
-           align_up((size_t)8 * shape->batch * shape->n_q_heads * sizeof(int32_t), 256);
+           align_up((size_t)8 * shape->batch * shape->n_q_heads * sizeof(int32_t), 256) +
+           scores_bytes(shape, n_dense_heads);  // the score maps, when the caller does not want them back
   return SP_OK;
 }
 
@@ -928,8 +934,12 @@ static sp_status prefill_impl(const sp_shape *shape, const void *q, const void *
   if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k")) || (rc = check_ptr16(v, "v")) ||
       (rc = check_ptr16(o, "o")))
     return rc;
-  if (!head_to_cluster || !pivot_heads || !block_scores || !kb_idx || !kb_cnt) {
-    set_err("head_to_cluster / pivot_heads / block_scores / kb_idx / kb_cnt must not be NULL");
+  if (!head_to_cluster || !pivot_heads || !kb_idx || !kb_cnt) {
+    set_err("head_to_cluster / pivot_heads / kb_idx / kb_cnt must not be NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (block_scores && ((uintptr_t)block_scores % 4)) {
+    set_err("block_scores is misaligned");
     return SP_ERR_INVALID_ARG;
   }
   if ((score_mode != SP_SCORE_BLOCK_MASS && score_mode != SP_SCORE_MEAN_LOGIT) ||
@@ -978,11 +988,13 @@ static sp_status prefill_impl(const sp_shape *shape, const void *q, const void *
   const PatternLayout PL = pattern_layout(shape, n_clusters);
   const PatternLayout PG = pattern_layout(shape, Hq);  // the gate pools every head
   const size_t off_tab = off_pat + (pattern_ws ? (gated ? PG.total : PL.total) : 0);
-  const size_t need = off_tab + (gated ? align_up((size_t)8 * shape->batch * Hq * sizeof(int32_t), 256) : 0);
+  const size_t off_sc = off_tab + (gated ? align_up((size_t)8 * shape->batch * Hq * sizeof(int32_t), 256) : 0);
+  const size_t need = off_sc + (block_scores ? 0 : scores_bytes(shape, n_clusters));
   if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   const int nqb = shape->seq / shape->block;
   char *ws = (char *)workspace;
+  if (!block_scores) block_scores = (float *)(ws + off_sc);  // the caller does not want the maps back
 
   if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
   // 1. pivots: dense attention (Alg. 4: no pattern yet => all ones) and their block score map
@@ -1328,47 +1340,6 @@ sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, 
   return sp_prefill_layer_modes(shape, q, k, v, head_to_cluster, pivot_heads, n_clusters, gamma, SP_SCORE_BLOCK_MASS,
                                 SP_SELECT_PER_ROW, o, block_scores, kb_idx, kb_cnt, workspace, workspace_bytes,
                                 hip_stream);
-}
-
-sp_status sp_probe_step_mix(int32_t mix, const void *operands, size_t operand_bytes, int32_t iters, float *sink,
-                            size_t sink_bytes, double *mfma_flops, void *hip_stream) {
-  g_err[0] = 0;
-  if (!operands || !sink || !mfma_flops) {
-    set_err("operands / sink / mfma_flops must not be NULL");
-    return SP_ERR_INVALID_ARG;
-  }
-  if (((uintptr_t)operands & 15) || operand_bytes < SP_PROBE_OPERAND_BYTES || sink_bytes < SP_PROBE_SINK_BYTES) {
-    set_err("operands must be 16-byte aligned and hold %zu bytes, sink %zu bytes", (size_t)SP_PROBE_OPERAND_BYTES,
-            (size_t)SP_PROBE_SINK_BYTES);
-    return SP_ERR_INVALID_ARG;
-  }
-  if (mix < SP_PROBE_MFMA || mix > SP_PROBE_STEP_64Q || iters < 1 || iters > 1000000) {
-    set_err("mix %d outside [0, 4] or iters %d outside [1, 1000000]", mix, iters);
-    return SP_ERR_INVALID_ARG;
-  }
-  int dev = 0, cus = 0;
-  sp_status rc;
-  if ((rc = hip_check(hipGetDevice(&dev), "hipGetDevice"))) return rc;
-  if ((rc = hip_check(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev),
-                      "hipDeviceGetAttribute")))
-    return rc;
-  // two workgroups of four wavefronts per CU (80 KiB of LDS each), one for the 64-query mix (160 KiB)
-  const int wg_per_cu = mix == SP_PROBE_STEP_64Q ? 1 : 2;
-  const int n_wg = cus * wg_per_cu;
-  if (cus < 1 || (size_t)n_wg * 256 * sizeof(float) > SP_PROBE_SINK_BYTES) {
-    set_err("device reports %d compute units", cus);
-    return SP_ERR_UNSUPPORTED;
-  }
-  const int g = mix == SP_PROBE_STEP_64Q ? 64 : 32;
-  *mfma_flops = (double)n_wg * 4 * (double)iters * g * (2.0 * 32 * 32 * 16);
-  hipStream_t st = (hipStream_t)hip_stream;
-  switch (mix) {
-    case SP_PROBE_MFMA: return launch_probe<0, 0, 0, 0, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
-    case SP_PROBE_LDS_READ: return launch_probe<1, 0, 0, 0, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
-    case SP_PROBE_RING: return launch_probe<1, 8, 0, 0, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
-    case SP_PROBE_STEP: return launch_probe<1, 8, 4, 1, 32, 80 * 1024>(operands, sink, iters, n_wg, st);
-    default: return launch_probe<2, 8, 4, 1, 64, 160 * 1024>(operands, sink, iters, n_wg, st);
-  }
 }
 
 }  // extern "C"

@@ -6,7 +6,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
-#include <vector>
+#include <mutex>
 
 #include "shareprefill.h"
 
@@ -24,33 +24,35 @@ constexpr int KT = 64;  // keys per sub-tile
 
 thread_local char g_err[512] = "";
 
-// Optional per-kernel timing (sp_profile_enable / sp_profile_read): every launch is bracketed
-// by two HIP events on the caller's stream.  Process-wide, not thread-safe; meant for benches.
+// Optional per-kernel timing for benchmarks (sp_profile_enable / sp_profile_read): while enabled, every
+// launch is bracketed by two HIP events on the caller's stream, taken from a fixed pool that
+// sp_profile_enable created beforehand (nothing is created or freed while work is being enqueued; launches
+// beyond the pool are counted as dropped and reported by the next read).  Process-wide.
 enum KernelKind { KK_PACK = 0, KK_DENSE = 1, KK_MASK = 2, KK_SPARSE = 3, KK_SCORE = 4, KK_VS = 5, KK_COUNT = 6 };
-struct ProfRec {
-  int kind;
-  hipEvent_t e0, e1;
-};
+constexpr int SP_PROF_CAPACITY = 4096;
 bool g_prof_on = false;
-std::vector<ProfRec> g_prof;
+hipEvent_t *g_prof_events = nullptr;  // 2 * SP_PROF_CAPACITY, pairs (begin, end)
+int g_prof_kind[SP_PROF_CAPACITY];
+int g_prof_count = 0, g_prof_dropped = 0;
+std::mutex g_prof_mutex;
 
 struct ProfScope {
   hipStream_t st;
-  bool on;
-  ProfRec rec;
-  ProfScope(int kind, hipStream_t s) : st(s), on(g_prof_on) {
-    if (!on) return;
-    rec.kind = kind;
-    if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) {
-      on = false;
+  int slot = -1;
+  ProfScope(int kind, hipStream_t s) : st(s) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (!g_prof_on || !g_prof_events) return;
+    if (g_prof_count >= SP_PROF_CAPACITY) {
+      ++g_prof_dropped;
       return;
     }
-    (void)hipEventRecord(rec.e0, st);
+    slot = g_prof_count++;
+    g_prof_kind[slot] = kind;
+    (void)hipEventRecord(g_prof_events[2 * slot], st);
   }
   ~ProfScope() {
-    if (!on) return;
-    (void)hipEventRecord(rec.e1, st);
-    g_prof.push_back(rec);
+    if (slot >= 0) (void)hipEventRecord(g_prof_events[2 * slot + 1], st);
   }
 };
 

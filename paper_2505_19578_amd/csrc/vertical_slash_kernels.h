@@ -39,6 +39,7 @@ __global__ __launch_bounds__(256) void vs_logits_kernel(VsParams p) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, c = lane & 31;
   const int head = p.head_ids[n];
   const int s0 = blockIdx.x * 128 + 32 * w;
+  if (s0 >= p.seq) return;  // seq is a multiple of 64, not necessarily of 128 (no barrier below)
   const uint16_t *kp = p.k + (int64_t)b * p.k_sb + (int64_t)(s0 + c) * p.k_st + (int64_t)(head / p.group) * p.k_sh + 8 * h;
   bf16x8 kf[DS];
 #pragma unroll

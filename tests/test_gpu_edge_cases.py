@@ -232,9 +232,9 @@ def test_pattern_calls_batch2_interleaved_qkv_and_custom_scale():
         assert abs(d_h[1, 1] - oracle.js_distance(est[1], est[0])) <= 2e-5 and d_h[0, 1] == 0.0 and d_h[2, 1] == 0.0
 
 
-@pytest.mark.parametrize("N,B,d", [(128, 128, 128), (128, 64, 64), (384, 128, 64)])
+@pytest.mark.parametrize("N,B,d", [(128, 128, 128), (128, 64, 64), (384, 128, 64), (192, 64, 64), (320, 64, 128)])
 def test_shortest_sequences_through_every_layer_call(N, B, d):
-    """One, two and three query blocks: the printed construction, the gate, the dictionary over two layers and
+    """One, two, three and five query blocks (two lengths are multiples of block = 64 but not of 128): the printed construction, the gate, the dictionary over two layers and
     the vertical-slash fallback all against the oracle's own runs (every row, every head)."""
     import torch
     import oracle
@@ -302,3 +302,22 @@ def test_shortest_sequences_through_every_layer_call(N, B, d):
                     ref_o, _, _ = oracle.dense_rows(hq[:, h], hk[:, g], hv[:, g], B, want_scores=False)
                 emax, emean = _err(o[0, :, h].float().cpu().numpy(), ref_o)
                 assert emax <= OUT_MAX and emean <= OUT_MEAN, f"layer {l} head {h} role {role_h[h]}: {emax} / {emean}"
+
+
+def test_fused_layer_without_returned_scores():
+    """block_scores = NULL: the score maps stay in the workspace; lists, counts and outputs are the same bits."""
+    import torch
+    import paper_2505_19578_amd as sp
+    from synth import CONFIGS, make_layer
+    from tests.gpu_util import to_dev, alloc_layer
+    L = make_layer(CONFIGS["llama8b_32k"], seq=1024)
+    cfg = L["cfg"]
+    q, k, v = (to_dev(L[x]) for x in "qkv")
+    C = cfg.n_clusters
+    shape, o, ws, scores, kb_idx, kb_cnt = alloc_layer(sp, cfg, q, k, C)
+    sp.sp_prefill_layer(shape, q, k, v, L["head_to_cluster"], L["pivot_heads"], cfg.gamma, o, scores, kb_idx, kb_cnt, ws)
+    o2, idx2, cnt2 = torch.zeros_like(o), torch.full_like(kb_idx, -5), torch.full_like(kb_cnt, -5)
+    sp.sp_prefill_layer(shape, q, k, v, L["head_to_cluster"], L["pivot_heads"], cfg.gamma, o2, None, idx2, cnt2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx2, kb_idx) and torch.equal(cnt2, kb_cnt)
+    assert torch.equal(o2.view(torch.int16), o.view(torch.int16))
