@@ -64,6 +64,12 @@ class LayerConfig:
     heavy_boost: float = 10.0  # logit boost of the heavy vertical keys
     value_gain: float = 4.0    # topic-dependent mean of V (nu)
     value_noise: float = 1.0   # std of the i.i.d. part of V (epsilon ~ N(0,1), as the workload statement gives it)
+    # Optional spread of head behaviour (entry (cluster * cluster_size + rank of the head inside its cluster, by head
+    # index) modulo the tuple's length): a multiplier on the query's topic gain (small = diffuse attention, large =
+    # highly sparse) and a shift of the topic ids the query follows (non-zero = a head whose pattern differs from
+    # its cluster's).
+    query_gain: Optional[tuple] = None
+    topic_shift: Optional[tuple] = None
 
     @property
     def cluster_size(self) -> int:
@@ -85,6 +91,12 @@ CONFIGS: Dict[str, LayerConfig] = {
     "qwen7b_128k": LayerConfig("qwen7b_128k", 4, 131072, 28, 4, 128, 128, 7, 0.9, 8, 16, "perm"),
     "llama70b_128k": LayerConfig("llama70b_128k", 5, 131072, 64, 8, 128, 128, 16, 0.95, 8, 16, "contig",
                                  n_layers=4),
+    # The Llama-3-8B shape with a spread of head sparsities inside every cluster, so that the thresholds the paper
+    # states (gamma 0.9, tau 0.2, delta 0.3) split the heads into dense pivots, pattern-sharing heads, heads whose
+    # pattern is not similar enough and highly sparse heads that are excluded from sharing.
+    "llama8b_128k_regime": LayerConfig("llama8b_128k_regime", 6, 131072, 32, 8, 128, 128, 8, 0.9, 8, 16, "contig",
+                                       query_gain=(0.04, 0.05, 0.04, 0.045, 0.04, 0.05, 0.04, 1.0),
+                                       topic_shift=(0, 0, 0, 3, 0, 0, 0, 0)),
 }
 
 
@@ -167,10 +179,17 @@ def make_layer(cfg: LayerConfig, layer: int = 0, seq: Optional[int] = None,
     k = np.empty((N, Hkv, d), dtype=np.uint16)
     v = np.empty((N, Hkv, d), dtype=np.uint16)
 
+    rank_in_cluster = np.zeros(Hq, dtype=np.int64)
+    for c in range(C):
+        for pos, h in enumerate(np.nonzero(h2c == c)[0]):
+            rank_in_cluster[h] = pos
     for h in range(Hq):
         c = int(h2c[h])
         x = _rng(seed, 1, h).standard_normal((N, d), dtype=np.float32)
-        x += (g * A[c])[topics[c]]
+        pos = c * cfg.cluster_size + int(rank_in_cluster[h])
+        gh = g * float(np.sqrt(cfg.query_gain[pos % len(cfg.query_gain)])) if cfg.query_gain else g
+        shift = int(cfg.topic_shift[pos % len(cfg.topic_shift)]) if cfg.topic_shift else 0
+        x += (gh * A[c])[(topics[c] + shift) % cfg.rank]
         x += cfg.sink_beta * e_s
         q[:, h, :] = f32_to_bf16_bits(x)
     for kv in range(Hkv):

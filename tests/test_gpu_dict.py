@@ -236,3 +236,16 @@ def test_dict_permuted_clusters_with_fallbacks():
     g = _run_and_check("qwen7b_128k", 4096, 2, float(0.5 * (ds[i] + ds[i + 1])), 10.0, label="qwen7b@4k sparsity gate")
     roles = np.array([x["role"] for x in g])
     assert (roles == -1).any() and (roles >= 0).any()
+
+
+def test_dict_paper_thresholds_on_the_spread_workload():
+    """The thresholds the paper states (Sec. 6.1 "Implementation Details": gamma 0.9, tau 0.2, delta 0.3) on the
+    workload whose heads spread in sparsity: every layer has heads that share, heads that fall back because they
+    are highly sparse or not similar enough, and the first layer elects the pivots; roles, distances, dictionary
+    and outputs against the oracle's head-by-head run."""
+    g = _run_and_check("llama8b_128k_regime", 4096, 2, 0.3, 0.2, label="regime@4k paper thresholds")
+    roles = np.array([x["role"] for x in g])
+    assert (roles[0] == -2).sum() >= 6 and (roles[0] >= 0).any() and (roles[0] == -1).any()
+    assert (roles[1] >= 0).sum() > (roles[1] == -1).sum() > 0
+    ds = g[0]["dist"][:, 0]
+    assert ds.min() < 0.3 < ds.max(), "the workload must straddle the sparsity threshold"
