@@ -84,6 +84,9 @@ def _load():
         L.spo_select_cumulative.argtypes = [fp, ctypes.c_int64, ctypes.c_float, up, ctypes.POINTER(ctypes.c_int64)]
         L.spo_vs_block_lists.restype = ctypes.c_int
         L.spo_vs_block_lists.argtypes = [up, up, ctypes.c_int, ctypes.c_int, ctypes.c_int, ip, ip]
+        L.spo_vs_token_rows.restype = ctypes.c_int
+        L.spo_vs_token_rows.argtypes = [fp, fp, fp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                        ctypes.POINTER(ctypes.c_int), ctypes.c_int, up, up, ctypes.c_int, fp]
         L.spo_js_distance.restype = ctypes.c_int
         L.spo_js_distance.argtypes = [fp, fp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
         _lib = L
@@ -295,6 +298,30 @@ def vs_block_lists(keep_v, keep_s, block: int, forced: bool = True):
     if rc:
         raise ValueError(f"spo_vs_block_lists failed ({rc})")
     return idx, cnt
+
+
+def vs_token_rows(q, k, v, block: int, keep_v, keep_s, forced: bool = True, rows: Optional[Sequence[int]] = None,
+                  scale: Optional[float] = None):
+    """Attention over the token-level vertical-slash pattern (Alg. 5's mask; Sec. 5.1 A(Q,K,V,M)): key s <= t is
+    allowed for query t iff keep_v[s] or keep_s[t - s] (or, forced, s lies in block 0 or in t's own block).
+    Returns O [len(rows) * block][d]."""
+    q, qp = _f(q)
+    k, kp = _f(k)
+    v, vp = _f(v)
+    N, d = q.shape
+    rows_a = _rows(rows, N // block)
+    keep_v = np.ascontiguousarray(keep_v, dtype=np.uint8)
+    keep_s = np.ascontiguousarray(keep_s, dtype=np.uint8)
+    assert keep_v.shape == (N,) and keep_s.shape == (N,)
+    scale = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    o = np.empty((len(rows_a) * block, d), dtype=np.float32)
+    up = ctypes.POINTER(ctypes.c_ubyte)
+    rc = _load().spo_vs_token_rows(qp, kp, vp, N, d, block, scale, rows_a.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
+                                   len(rows_a), keep_v.ctypes.data_as(up), keep_s.ctypes.data_as(up), int(bool(forced)),
+                                   o.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if rc:
+        raise ValueError(f"spo_vs_token_rows failed ({rc})")
+    return o
 
 
 def vertical_slash_pattern(q, k, block: int, gamma: float, scale: Optional[float] = None, forced: bool = True):

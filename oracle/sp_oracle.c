@@ -570,3 +570,72 @@ int spo_vs_block_lists(const unsigned char *keep_v, const unsigned char *keep_s,
   }
   return 0;
 }
+
+/*
+ * Attention over the vertical-slash pattern of Alg. 5 at token granularity (the mask M the algorithm builds from
+ * S = S_v U S_s): query t attends to key s <= t iff key s is kept (a vertical line), or offset t - s is kept
+ * (a slash line), or -- forced != 0 -- s lies in the first block or in t's own block (the sink and diagonal
+ * blocks every pattern of this library carries).  Excluded pairs get weight exactly 0 and the softmax is
+ * renormalised (Sec. 5.1); a query with no allowed key gets zeros.  rows: query-block rows to evaluate;
+ * o: [nrows * B][d].
+ */
+int spo_vs_token_rows(const float *q, const float *k, const float *v, int N, int d, int B, double scale,
+                      const int *rows, int nrows, const unsigned char *keep_v, const unsigned char *keep_s, int forced,
+                      float *o) {
+  if (N <= 0 || d <= 0 || B <= 0 || N % B) return 1;
+  const int nkb = N / B;
+  for (int r = 0; r < nrows; ++r)
+    if (rows[r] < 0 || rows[r] >= nkb) return 1;
+  int fail = 0;
+#pragma omp parallel
+  {
+    double *x = (double *)malloc(sizeof(double) * (size_t)N);
+    double *acc = (double *)malloc(sizeof(double) * (size_t)d);
+    unsigned char *on = (unsigned char *)malloc((size_t)N);
+    if (!x || !acc || !on) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int r = 0; r < nrows; ++r) {
+        const int i = rows[r];
+        for (int tt = 0; tt < B; ++tt) {
+          const int t = i * B + tt;
+          const float *qt = q + (size_t)t * d;
+          double mx = -INFINITY;
+          for (int s = 0; s <= t; ++s) {
+            on[s] = keep_v[s] || keep_s[t - s] || (forced && (s / B == 0 || s / B == i));
+            if (!on[s]) continue;
+            const float *ks = k + (size_t)s * d;
+            double a = 0.0;
+#pragma omp simd reduction(+ : a)
+            for (int e = 0; e < d; ++e) a += (double)qt[e] * (double)ks[e];
+            x[s] = a * scale;
+            if (x[s] > mx) mx = x[s];
+          }
+          double den = 0.0;
+          for (int s = 0; s <= t; ++s) {
+            if (!on[s]) continue;
+            x[s] = exp(x[s] - mx);
+            den += x[s];
+          }
+          for (int e = 0; e < d; ++e) acc[e] = 0.0;
+          if (den > 0.0) {
+            for (int s = 0; s <= t; ++s) {
+              if (!on[s]) continue;
+              const double p = x[s] / den;
+              const float *vs = v + (size_t)s * d;
+              for (int e = 0; e < d; ++e) acc[e] += p * (double)vs[e];
+            }
+          }
+          float *ot = o + ((size_t)r * B + tt) * d;
+          for (int e = 0; e < d; ++e) ot[e] = (float)acc[e];
+        }
+      }
+    }
+    free(x);
+    free(acc);
+    free(on);
+  }
+  return fail;
+}

@@ -159,3 +159,66 @@ def test_layer_functions_route_failing_and_unclustered_heads_to_the_vertical_sla
     for h in range(4):
         idx, cnt = oracle.vertical_slash_pattern(q[:, h], k[:, h // 2], B, 0.6)[:2]
         assert np.array_equal(res[0]["o"][:, h], oracle.masked_rows(q[:, h], k[:, h // 2], v[:, h // 2], B, idx, cnt))
+
+
+# ---- attention over the token-level pattern (Alg. 5's mask under Sec. 5.1's A(Q,K,V,M)) ----------------------
+def _token_brute(q, k, v, B, keep_v, keep_s, forced):
+    """fp64 numpy on the materialised N x N boolean mask."""
+    N, d = q.shape
+    t, s = np.arange(N)[:, None], np.arange(N)[None, :]
+    allow = (s <= t) & (keep_v.astype(bool)[None, :] | keep_s.astype(bool)[np.clip(t - s, 0, N - 1)])
+    if forced:
+        allow |= (s <= t) & ((s // B == 0) | (s // B == t // B))
+    x = (q.astype(np.float64) @ k.astype(np.float64).T) / np.sqrt(d)
+    x = np.where(allow, x, -np.inf)
+    mx = np.where(np.isfinite(x.max(1, keepdims=True)), x.max(1, keepdims=True), 0.0)
+    p = np.where(allow, np.exp(x - mx), 0.0)
+    den = p.sum(1, keepdims=True)
+    return np.where(den > 0, p / np.where(den > 0, den, 1.0), 0.0) @ v.astype(np.float64), allow
+
+
+@pytest.mark.parametrize("forced", [True, False])
+def test_token_pattern_attention_vs_materialised_mask(forced):
+    rng = np.random.default_rng(31)
+    N, d, B = 192, 32, 32
+    q, k, v = (rng.standard_normal((N, d)).astype(np.float32) * 1.3 for _ in range(3))
+    keep_v = (rng.random(N) < 0.08).astype(np.uint8)
+    keep_s = (rng.random(N) < 0.05).astype(np.uint8)
+    keep_s[0] = 0                       # without forced blocks some queries then have no allowed key at all
+    want, allow = _token_brute(q, k, v, B, keep_v, keep_s, forced)
+    got = oracle.vs_token_rows(q, k, v, B, keep_v, keep_s, forced)
+    assert np.abs(got - want).max() <= 1e-5
+    if not forced:
+        empty = ~allow.any(1)
+        assert empty.any() and np.all(got[empty] == 0.0)
+    rows = [1, 4]
+    sub = oracle.vs_token_rows(q, k, v, B, keep_v, keep_s, forced, rows=rows)
+    assert np.array_equal(sub, np.concatenate([got[i * B:(i + 1) * B] for i in rows]))
+
+
+def test_token_pattern_attention_special_cases():
+    rng = np.random.default_rng(32)
+    N, d, B = 128, 16, 32
+    q, k, v = (rng.standard_normal((N, d)).astype(np.float32) for _ in range(3))
+    zeros, ones = np.zeros(N, np.uint8), np.ones(N, np.uint8)
+    dense, _, _ = oracle.dense_rows(q, k, v, B, want_scores=False)
+    # every key kept, or every offset kept: the causal dense result
+    assert np.abs(oracle.vs_token_rows(q, k, v, B, ones, zeros, False) - dense).max() <= 1e-6
+    assert np.abs(oracle.vs_token_rows(q, k, v, B, zeros, ones, False) - dense).max() <= 1e-6
+    # only offset 0: every query sees itself alone
+    only0 = zeros.copy(); only0[0] = 1
+    assert np.abs(oracle.vs_token_rows(q, k, v, B, zeros, only0, False) - v).max() <= 1e-6
+    # one vertical line at s0: v[s0] from t = s0 on, nothing before
+    s0 = 37
+    one = zeros.copy(); one[s0] = 1
+    got = oracle.vs_token_rows(q, k, v, B, one, zeros, False)
+    assert np.all(got[:s0] == 0.0) and np.abs(got[s0:] - v[s0]).max() <= 1e-6
+    # nothing kept but the forced blocks: the block pattern {0, i}
+    idx, cnt = oracle.vs_block_lists(zeros, zeros, B, True)
+    assert np.abs(oracle.vs_token_rows(q, k, v, B, zeros, zeros, True) - oracle.masked_rows(q, k, v, B, idx, cnt)).max() <= 1e-6
+    # the token pattern never holds more than its block superset: a kept key in a block lists the whole block
+    kv = zeros.copy(); kv[40] = 1
+    idx, cnt = oracle.vs_block_lists(kv, zeros, B, True)
+    tok = oracle.vs_token_rows(q, k, v, B, kv, zeros, True)
+    blk = oracle.masked_rows(q, k, v, B, idx, cnt)
+    assert np.abs(tok[:B] - blk[:B]).max() <= 1e-6 and np.abs(tok[2 * B:] - blk[2 * B:]).max() > 1e-3
