@@ -281,8 +281,10 @@ sp_status sp_prefill_layer_gated(const sp_shape *shape, const void *q, const voi
                                  int32_t *head_pattern, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* What a head does when Alg. 3 sends it to the fallback pattern. */
-enum { SP_FALLBACK_DENSE = 0,            /* dense causal attention (exact) */
-       SP_FALLBACK_VERTICAL_SLASH = 1 }; /* the pattern of Alg. 5 */
+enum { SP_FALLBACK_DENSE = 0,                  /* dense causal attention (exact) */
+       SP_FALLBACK_VERTICAL_SLASH = 1,         /* the pattern of Alg. 5 widened to whole key blocks
+                                                  (sp_search_vertical_slash + block-sparse attention) */
+       SP_FALLBACK_VERTICAL_SLASH_TOKEN = 2 }; /* the pattern of Alg. 5 token by token (sp_vertical_slash_attn) */
 
 /* Workspace of sp_search_vertical_slash for n_heads listed heads (block * seq * 4 bytes per head and more). */
 sp_status sp_vs_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *bytes);
@@ -307,6 +309,31 @@ sp_status sp_vs_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *
 sp_status sp_search_vertical_slash(const sp_shape *shape, const void *q, const void *k, const int32_t *head_ids,
                                    int32_t n_heads, float gamma, int32_t forced, float *sums, int32_t *kb_idx,
                                    int32_t *kb_cnt, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Workspace of sp_vertical_slash_attn for n_heads listed heads (the search's, the packed K/V copy and one more
+ * packed copy of K and V per listed head for its gathered keys). */
+sp_status sp_vs_token_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *bytes);
+
+/*
+ * Alg. 5 (Search Vertical Slash Pattern) for the listed heads, as sp_search_vertical_slash forms it (Q_hat = the
+ * last `block` queries, the two vector selections at `gamma`), followed by attention A(Q,K,V,M) (Sec. 5.1) over
+ * the mask M the algorithm builds from S = S_v U S_s, token by token: query t attends to key s <= t iff key s is
+ * kept (a vertical line) or offset t - s is kept (a slash line) or -- forced != 0 -- s lies in the first block or
+ * in t's own block (the sink and diagonal blocks every pattern of this library carries).  Pairs outside M get
+ * weight exactly 0, the softmax is renormalised, a query without any allowed key gets zeros.
+ * The kept keys are gathered into packed images of their own (64 keys each), the kept offsets are walked as bands
+ * of key blocks with a bit mask inside every tile; no whole block is attended to because of one kept key.
+ *   head_ids  host [n_heads] distinct query heads
+ *   o         device bf16; only the listed heads' rows are written
+ *   keep_bits device uint64 [batch][n_heads][2][seq/64] or NULL  (output: bit s of the first vector = key s kept,
+ *             bit o of the second = offset o kept)
+ *   pairs     device int64 [batch][n_heads] or NULL  (output: number of (query, key) pairs in M)
+ *   workspace sp_vs_token_workspace_bytes(shape, n_heads)
+ */
+sp_status sp_vertical_slash_attn(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                 const int32_t *head_ids, int32_t n_heads, float gamma, int32_t forced, void *o,
+                                 uint64_t *keep_bits, int64_t *pairs, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream);
 
 /*
  * The dynamic pivotal pattern dictionary (Sec. 5.2, "Dynamic Pattern Construction and Sharing
@@ -336,7 +363,9 @@ typedef struct {
  *   Heads with cluster -1 and fallback heads (role -1) never touch the dictionary; with
  *   fallback_mode SP_FALLBACK_DENSE they run dense attention, with SP_FALLBACK_VERTICAL_SLASH
  *   each gets its own pattern from Alg. 5 (sp_search_vertical_slash with the layer's gamma, forced
- *   blocks on) and runs block-sparse over it.  Everything is decided on the device: one stream, no
+ *   blocks on) and runs block-sparse over it, with SP_FALLBACK_VERTICAL_SLASH_TOKEN each runs
+ *   sp_vertical_slash_attn's token-level attention over that pattern (vs_idx / vs_cnt unused).
+ *   Everything is decided on the device: one stream, no
  *   host synchronisation; the roles can be read back afterwards.
  *   head_to_cluster host [n_q_heads] global cluster id in [0, dict->n_clusters) or -1
  *   block_scores    device fp32 [batch][n_slots][nqb][nkb], n_slots = number of distinct clusters
@@ -350,7 +379,8 @@ typedef struct {
  *                   the heads that took the vertical-slash fallback (other heads' entries are left
  *                   untouched); may be NULL with SP_FALLBACK_DENSE
  *   workspace       sp_workspace_bytes(shape, n_slots), plus sp_vs_workspace_bytes(shape, n_q_heads)
- *                   with SP_FALLBACK_VERTICAL_SLASH
+ *                   with SP_FALLBACK_VERTICAL_SLASH, or sp_vs_token_workspace_bytes(shape, n_q_heads)
+ *                   with SP_FALLBACK_VERTICAL_SLASH_TOKEN
  */
 sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void *k, const void *v,
                                 const int32_t *head_to_cluster, float gamma, float delta, float tau,

@@ -15,6 +15,7 @@ from .binding import (SpError, SpShape, lib, shape_of, sp_workspace_bytes, sp_pr
                       sp_determine_pattern, sp_block_sparse_attn_gated, sp_prefill_layer_gated,
                       sp_prefill_layer_dict, pattern_dict_of, SpPatternDict,
                       sp_vs_workspace_bytes, sp_search_vertical_slash, SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH,
+                      SP_FALLBACK_VERTICAL_SLASH_TOKEN, sp_vs_token_workspace_bytes, sp_vertical_slash_attn,
                       SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT, SP_SELECT_PER_ROW, SP_SELECT_GLOBAL,
                       )
 
@@ -27,5 +28,6 @@ __all__ = ["SpError", "SpShape", "lib", "shape_of", "sp_workspace_bytes", "sp_pr
            "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated",
            "sp_prefill_layer_dict", "pattern_dict_of", "SpPatternDict",
            "sp_vs_workspace_bytes", "sp_search_vertical_slash", "SP_FALLBACK_DENSE", "SP_FALLBACK_VERTICAL_SLASH",
+           "SP_FALLBACK_VERTICAL_SLASH_TOKEN", "sp_vs_token_workspace_bytes", "sp_vertical_slash_attn",
            "SP_SCORE_BLOCK_MASS", "SP_SCORE_MEAN_LOGIT", "SP_SELECT_PER_ROW", "SP_SELECT_GLOBAL",
            ]

@@ -18,10 +18,10 @@ EXPORTED_SYMBOLS = [
     "sp_score_workspace_bytes", "sp_mask_workspace_bytes", "sp_block_mean_logit_scores",
     "sp_build_block_mask_global", "sp_build_block_mask_global_static", "sp_prefill_layer_modes",
     "sp_determine_pattern", "sp_block_sparse_attn_gated", "sp_prefill_layer_gated", "sp_prefill_layer_dict",
-    "sp_vs_workspace_bytes", "sp_search_vertical_slash",
+    "sp_vs_workspace_bytes", "sp_search_vertical_slash", "sp_vs_token_workspace_bytes", "sp_vertical_slash_attn",
 ]
 
-SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH = 0, 1
+SP_FALLBACK_DENSE, SP_FALLBACK_VERTICAL_SLASH, SP_FALLBACK_VERTICAL_SLASH_TOKEN = 0, 1, 2
 SP_STATIC_SCRATCH_BYTES = 2 << 20
 
 SP_SCORE_BLOCK_MASS, SP_SCORE_MEAN_LOGIT = 0, 1
@@ -122,6 +122,11 @@ def lib() -> ctypes.CDLL:
         L.sp_search_vertical_slash.restype = ctypes.c_int
         L.sp_search_vertical_slash.argtypes = [sp, vp, vp, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_int32, fp, vp,
                                                vp, vp, ctypes.c_size_t, vp]
+        L.sp_vs_token_workspace_bytes.restype = ctypes.c_int
+        L.sp_vs_token_workspace_bytes.argtypes = [sp, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
+        L.sp_vertical_slash_attn.restype = ctypes.c_int
+        L.sp_vertical_slash_attn.argtypes = [sp, vp, vp, vp, ip, ctypes.c_int32, ctypes.c_float, ctypes.c_int32, vp, vp,
+                                             vp, vp, ctypes.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -309,3 +314,16 @@ def sp_search_vertical_slash(shape: SpShape, q, k, head_ids, gamma: float, force
     _check(lib().sp_search_vertical_slash(
         ctypes.byref(shape), _ptr(q), _ptr(k), _ids(head_ids), len(head_ids), ctypes.c_float(gamma),
         1 if forced else 0, _ptr(sums), _ptr(kb_idx), _ptr(kb_cnt), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def sp_vs_token_workspace_bytes(shape: SpShape, n_heads: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().sp_vs_token_workspace_bytes(ctypes.byref(shape), n_heads, ctypes.byref(n)))
+    return int(n.value)
+
+
+def sp_vertical_slash_attn(shape: SpShape, q, k, v, head_ids, gamma: float, forced: bool, o, keep_bits, pairs,
+                           workspace):
+    _check(lib().sp_vertical_slash_attn(
+        ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ids(head_ids), len(head_ids), ctypes.c_float(gamma),
+        1 if forced else 0, _ptr(o), _ptr(keep_bits), _ptr(pairs), _ptr(workspace), _nbytes(workspace), _stream()))

@@ -246,9 +246,11 @@ __global__ __launch_bounds__(256) void gsel_emit_kernel(const float *__restrict_
 }
 
 // Selection over plain vectors (rectangular geometry): per (map, row) two flags instead of a list:
-// bit 0 = some entry of the row is kept, bit 1 = some entry other than the row's first is kept.
+// bit 0 = some entry of the row is kept, bit 1 = some entry other than the row's first is kept.  bits (optional,
+// n_cols a multiple of 64): the kept set itself, one bit per vector entry, [n_maps][n_rows * n_cols / 64] words.
 __global__ __launch_bounds__(256) void gsel_emit_flags_kernel(const float *__restrict__ scores, GselGeom g, char *scratch,
-                                                              int32_t *__restrict__ flags) {
+                                                              int32_t *__restrict__ flags,
+                                                              uint64_t *__restrict__ bits = nullptr) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), map = blockIdx.y;
   if (row >= g.n_rows || gsel_skip(g, map)) return;
@@ -272,6 +274,7 @@ __global__ __launch_bounds__(256) void gsel_emit_flags_kernel(const float *__res
     const uint64_t smask = __ballot(sel);
     any |= smask != 0ull;
     any_after_first |= (j0 == 0 ? (smask & ~1ull) : smask) != 0ull;
+    if (bits && lane == 0) bits[((int64_t)map * g.n_rows + row) * (g.n_cols / 64) + j0 / 64] = smask;
   }
   if (lane == 0) flags[(int64_t)map * g.n_rows + row] = any | (any_after_first << 1);
 }

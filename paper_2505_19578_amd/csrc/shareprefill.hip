@@ -47,6 +47,7 @@
 #include "pattern_kernels.h"
 #include "global_select_kernels.h"
 #include "vertical_slash_kernels.h"
+#include "vs_token_kernels.h"
 
 namespace {
 
@@ -419,7 +420,8 @@ VsLayout vs_layout(const sp_shape *s, int n) {
 // entry is -1.  sums_out (optional, [b][n][2][seq]) receives a_v and a_s.
 sp_status launch_vertical_slash(const sp_shape *s, const void *q, const void *k, const int32_t *heads, int n,
                                 float gamma, int forced, const int32_t *role, int by_head, float *sums_out,
-                                int32_t *kb_idx, int32_t *kb_cnt, char *vs_ws, hipStream_t st) {
+                                int32_t *kb_idx, int32_t *kb_cnt, char *vs_ws, hipStream_t st,
+                                uint64_t *keep_bits = nullptr) {
   if ((int64_t)s->batch * n * 2 > 65535) {
     set_err("batch * heads * 2 = %lld exceeds 65535", (long long)s->batch * n * 2);
     return SP_ERR_UNSUPPORTED;
@@ -478,10 +480,86 @@ sp_status launch_vertical_slash(const sp_shape *s, const void *q, const void *k,
   const uint32_t gq = (uint32_t)rintf(gamma * 16777216.f);
   launch_gsel_threshold(vp.sums, n_maps, g, gq, vs_ws + L.gsel, st);
   hipLaunchKernelGGL(gsel_emit_flags_kernel, dim3((nkb + 3) / 4, n_maps), dim3(256), 0, st, vp.sums, g,
-                     vs_ws + L.gsel, flags);
-  hipLaunchKernelGGL(vs_block_lists_kernel, dim3((nkb + 3) / 4, n, s->batch), dim3(256), 0, st, vp, flags, nkb, forced,
-                     by_head, kb_idx, kb_cnt);
+                     vs_ws + L.gsel, flags, keep_bits);
+  if (kb_idx)  // the pattern at block granularity (not needed by the token-level attention)
+    hipLaunchKernelGGL(vs_block_lists_kernel, dim3((nkb + 3) / 4, n, s->batch), dim3(256), 0, st, vp, flags, nkb,
+                       forced, by_head, kb_idx, kb_cnt);
   return hip_check(hipGetLastError(), "vertical-slash selection kernels launch");
+}
+
+// workspace of the token-level vertical-slash attention for n listed heads per batch entry, after the search's own
+struct VsTokLayout {
+  size_t search, bits, cumv, gpos, cumband, bandlist, gimg, total;
+};
+VsTokLayout vs_token_layout(const sp_shape *s, int n) {
+  const size_t maps = (size_t)s->batch * n, nqb = s->seq / s->block;
+  VsTokLayout L;
+  L.search = 0;
+  L.bits = L.search + vs_layout(s, n).total;
+  L.cumv = L.bits + align_up(maps * 2 * (s->seq / 64) * sizeof(uint64_t), 256);
+  L.gpos = L.cumv + align_up(maps * (nqb + 1) * sizeof(int32_t), 256);
+  L.cumband = L.gpos + align_up(maps * s->seq * sizeof(int32_t), 256);
+  L.bandlist = L.cumband + align_up(maps * nqb * sizeof(int32_t), 256);
+  L.gimg = L.bandlist + align_up(maps * nqb * sizeof(int32_t), 256);
+  L.total = L.gimg + align_up(maps * (size_t)s->seq * s->head_dim * 2 * 2, 256);
+  return L;
+}
+
+// Alg. 5 for the listed heads and attention over its token-level pattern.  kvp: the packed K/V images of the call.
+// role (device, [b][n_q_heads], heads listed 0..n_q_heads-1): only heads whose entry is -1 take part.
+sp_status launch_vs_token_attn(const sp_shape *s, const void *q, const void *k, const void *v, const char *kvp,
+                               const int32_t *heads, int n, float gamma, int forced, const int32_t *role, void *o,
+                               uint64_t *keep_bits_out, int64_t *pairs, char *ws, hipStream_t st) {
+  const VsTokLayout L = vs_token_layout(s, n);
+  uint64_t *bits = keep_bits_out ? keep_bits_out : (uint64_t *)(ws + L.bits);
+  sp_status rc = launch_vertical_slash(s, q, k, heads, n, gamma, forced, role, 0, nullptr, nullptr, nullptr,
+                                       ws + L.search, st, bits);
+  if (rc) return rc;
+  VsTokParams tp;
+  memset(&tp, 0, sizeof(tp));
+  tp.q = (const uint16_t *)q;
+  tp.k = (const uint16_t *)k;
+  tp.v = (const uint16_t *)v;
+  tp.kvp = kvp;
+  tp.o = (uint16_t *)o;
+  tp.q_sb = s->q_stride_b, tp.q_st = s->q_stride_t, tp.q_sh = s->q_stride_h;
+  tp.kv_sb = s->kv_stride_b, tp.kv_st = s->kv_stride_t, tp.kv_sh = s->kv_stride_h;
+  tp.o_sb = s->o_stride_b, tp.o_st = s->o_stride_t, tp.o_sh = s->o_stride_h;
+  tp.seq = s->seq;
+  tp.nqb = s->seq / s->block;
+  tp.block = s->block;
+  tp.n_kv_heads = s->n_kv_heads;
+  tp.group = s->n_q_heads / s->n_kv_heads;
+  tp.n_heads = n;
+  tp.n_q_heads = s->n_q_heads;
+  tp.forced = forced;
+  const float scale = (s->softmax_scale > 0.f) ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
+  tp.c = scale * 1.4426950408889634f;
+  tp.bits = bits;
+  tp.cumv = (int32_t *)(ws + L.cumv);
+  tp.gpos = (int32_t *)(ws + L.gpos);
+  tp.cumband = (int32_t *)(ws + L.cumband);
+  tp.bandlist = (int32_t *)(ws + L.bandlist);
+  tp.gimg = ws + L.gimg;
+  tp.pairs = pairs;
+  tp.role = role;
+  for (int a = 0; a < n; ++a) tp.head_ids[a] = heads[a];
+  ProfScope prof(KK_VS, st);
+  hipLaunchKernelGGL(vs_token_prep_kernel, dim3(n, s->batch), dim3(1024), 0, st, tp);
+  const dim3 ggather(s->seq / KT, n, s->batch), gattn(tp.nqb, n, s->batch);
+  if (s->head_dim == 128)
+    hipLaunchKernelGGL(vs_gather_kernel<128>, ggather, dim3(256), 0, st, tp);
+  else
+    hipLaunchKernelGGL(vs_gather_kernel<64>, ggather, dim3(256), 0, st, tp);
+  if (s->head_dim == 128 && s->block == 128)
+    hipLaunchKernelGGL((vs_token_attn_kernel<128, 128>), gattn, dim3(256), 0, st, tp);
+  else if (s->head_dim == 128 && s->block == 64)
+    hipLaunchKernelGGL((vs_token_attn_kernel<128, 64>), gattn, dim3(128), 0, st, tp);
+  else if (s->head_dim == 64 && s->block == 128)
+    hipLaunchKernelGGL((vs_token_attn_kernel<64, 128>), gattn, dim3(256), 0, st, tp);
+  else
+    hipLaunchKernelGGL((vs_token_attn_kernel<64, 64>), gattn, dim3(128), 0, st, tp);
+  return hip_check(hipGetLastError(), "token-level vertical-slash kernels launch");
 }
 
 sp_status check_thresholds(float delta, float tau) {
@@ -1136,11 +1214,13 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
     return SP_ERR_INVALID_ARG;
   }
   if ((rc = check_thresholds(delta, tau))) return rc;
-  if (fallback_mode != SP_FALLBACK_DENSE && fallback_mode != SP_FALLBACK_VERTICAL_SLASH) {
+  if (fallback_mode != SP_FALLBACK_DENSE && fallback_mode != SP_FALLBACK_VERTICAL_SLASH &&
+      fallback_mode != SP_FALLBACK_VERTICAL_SLASH_TOKEN) {
     set_err("unknown fallback_mode %d", fallback_mode);
     return SP_ERR_INVALID_ARG;
   }
   const bool vs = fallback_mode == SP_FALLBACK_VERTICAL_SLASH;
+  const bool vst = fallback_mode == SP_FALLBACK_VERTICAL_SLASH_TOKEN;
   if (vs && (!vs_idx || !vs_cnt)) {
     set_err("vs_idx / vs_cnt must not be NULL with the vertical-slash fallback");
     return SP_ERR_INVALID_ARG;
@@ -1178,7 +1258,7 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
   const size_t off_pat = off_lws + (mass ? lws_bytes(shape, n_slots) : 0);
   const size_t off_tab = off_pat + PG.total;
   const size_t off_vs = off_tab + align_up((size_t)8 * shape->batch * Hq * sizeof(int32_t), 256);
-  const size_t need = off_vs + (vs ? vs_layout(shape, Hq).total : 0);
+  const size_t need = off_vs + (vs ? vs_layout(shape, Hq).total : 0) + (vst ? vs_token_layout(shape, Hq).total : 0);
   if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
   char *ws = (char *)workspace;
@@ -1263,6 +1343,11 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
     // 4. Alg. 5 for every head whose role is -1 (fallback and heads outside every cluster), lists per head
     if ((rc = launch_vertical_slash(shape, q, k, all, Hq, gamma, 1, role, 1, nullptr, vs_idx, vs_cnt, ws + off_vs, st)))
       return rc;
+  } else if (vst) {
+    // 4. Alg. 5 and attention over its token-level pattern for every head whose role is -1
+    if ((rc = launch_vs_token_attn(shape, q, k, v, (const char *)workspace, all, Hq, gamma, 1, role, o, nullptr,
+                                   nullptr, ws + off_vs, st)))
+      return rc;
   } else {
     // 4. heads outside every cluster: dense, no scores
     fill_attn(ap, shape, q, workspace, o);
@@ -1277,7 +1362,7 @@ sp_status sp_prefill_layer_dict(const sp_shape *shape, const void *q, const void
   //    pivot -> done above.  Two launches over the same slot table, each restricted on the device to one
   //    weight class (a list-walking head costs a fraction of a falling-back one) and spread over all XCDs.
   if (rl.n) {
-    for (int cls = 0; cls < 2; ++cls) {
+    for (int cls = 0; cls < (vst ? 1 : 2); ++cls) {  // token-level fallback heads are done already
       fill_attn(ap, shape, q, workspace, o);
       ap.n_maps = dict->n_clusters;
       ap.kb_idx = dict->kb_idx;
@@ -1331,6 +1416,53 @@ sp_status sp_search_vertical_slash(const sp_shape *shape, const void *q, const v
   if ((rc = check_ws(workspace, workspace_bytes, vs_layout(shape, n_heads).total))) return rc;
   return launch_vertical_slash(shape, q, k, head_ids, n_heads, gamma, forced != 0, nullptr, 0, sums, kb_idx, kb_cnt,
                                (char *)workspace, (hipStream_t)hip_stream);
+}
+
+sp_status sp_vs_token_workspace_bytes(const sp_shape *shape, int32_t n_heads, size_t *bytes) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if (!bytes) {
+    set_err("bytes is NULL");
+    return SP_ERR_INVALID_ARG;
+  }
+  if (n_heads < 0 || n_heads > shape->n_q_heads) {
+    set_err("n_heads %d outside [0, %d]", n_heads, shape->n_q_heads);
+    return SP_ERR_INVALID_ARG;
+  }
+  *bytes = pack_bytes(shape) + vs_token_layout(shape, n_heads).total;
+  return SP_OK;
+}
+
+sp_status sp_vertical_slash_attn(const sp_shape *shape, const void *q, const void *k, const void *v,
+                                 const int32_t *head_ids, int32_t n_heads, float gamma, int32_t forced, void *o,
+                                 uint64_t *keep_bits, int64_t *pairs, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream) {
+  g_err[0] = 0;
+  sp_status rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_ptr16(q, "q")) || (rc = check_ptr16(k, "k")) || (rc = check_ptr16(v, "v")) ||
+      (rc = check_ptr16(o, "o")))
+    return rc;
+  if ((rc = check_heads(shape, head_ids, n_heads, "head_ids"))) return rc;
+  if (!(gamma > 0.f) || gamma > 1.f) {
+    set_err("gamma %g outside (0, 1]", (double)gamma);
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((keep_bits && ((uintptr_t)keep_bits % 8)) || (pairs && ((uintptr_t)pairs % 8))) {
+    set_err("keep_bits / pairs must be 8-byte aligned");
+    return SP_ERR_INVALID_ARG;
+  }
+  if ((int64_t)shape->batch * n_heads * 2 > 65535) {
+    set_err("batch * heads * 2 = %lld exceeds 65535", (long long)shape->batch * n_heads * 2);
+    return SP_ERR_UNSUPPORTED;
+  }
+  const size_t need = pack_bytes(shape) + vs_token_layout(shape, n_heads).total;
+  if ((rc = check_ws(workspace, workspace_bytes, need))) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = launch_pack(shape, k, v, workspace, st))) return rc;
+  return launch_vs_token_attn(shape, q, k, v, (const char *)workspace, head_ids, n_heads, gamma, forced != 0, nullptr,
+                              o, keep_bits, pairs, (char *)workspace + pack_bytes(shape), st);
 }
 
 sp_status sp_prefill_layer(const sp_shape *shape, const void *q, const void *k, const void *v,
