@@ -66,8 +66,9 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
     shape = sp.shape_of(dev[0]["q"], dev[0]["k"], None, B)
     outs = [torch.zeros_like(dv["q"]) for dv in dev]
     vs = args.fallback == "vs"
-    ws = torch.empty(sp.sp_workspace_bytes(shape, C) + (sp.sp_vs_workspace_bytes(shape, Hq) if vs else 0),
-                     dtype=torch.uint8, device="cuda")
+    vst = args.fallback == "vs-token"
+    ws = torch.empty(sp.sp_workspace_bytes(shape, C) + (sp.sp_vs_workspace_bytes(shape, Hq) if vs else 0)
+                     + (sp.sp_vs_token_workspace_bytes(shape, Hq) if vst else 0), dtype=torch.uint8, device="cuda")
     vs_idx = torch.empty((1, Hq, nqb, nqb), dtype=torch.int32, device="cuda") if vs else None
     vs_cnt = torch.zeros((1, Hq, nqb), dtype=torch.int32, device="cuda") if vs else None
     scores = torch.empty((1, C, nqb, nqb), dtype=torch.float32, device="cuda")
@@ -85,7 +86,8 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
         for l in range(nl):
             sp.sp_prefill_layer_dict(shape, dev[l]["q"], dev[l]["k"], dev[l]["v"], h2c, cfg.gamma, delta, tau,
                                      score_mode, select_mode, pd, outs[l], scores, roles[l], a_hat, dist, ws,
-                                     fallback_mode=sp.SP_FALLBACK_VERTICAL_SLASH if vs else sp.SP_FALLBACK_DENSE,
+                                     fallback_mode=(sp.SP_FALLBACK_VERTICAL_SLASH if vs else
+                                                    sp.SP_FALLBACK_VERTICAL_SLASH_TOKEN if vst else sp.SP_FALLBACK_DENSE),
                                      vs_idx=vs_idx, vs_cnt=vs_cnt)
 
     for _ in range(args.warmup):
@@ -120,6 +122,17 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
             else:
                 tiles += dense_tiles_per_head
     dense_equiv_flops = nl * Hq * 4.0 * d * (N * (N + 1) / 2.0)
+    # token-level fallback: the pattern's size (pairs kept / causal pairs) of the last layer's fallback heads, from
+    # one stand-alone call outside the timed region
+    pair_frac = None
+    if vst:
+        fb = [h for h in range(Hq) if role_h[-1][h] == -1]
+        if fb:
+            pairs = torch.zeros((1, len(fb)), dtype=torch.int64, device="cuda")
+            sp.sp_vertical_slash_attn(shape, dev[-1]["q"], dev[-1]["k"], dev[-1]["v"], fb, cfg.gamma, True,
+                                      torch.zeros_like(outs[-1]), None, pairs, ws)
+            torch.cuda.synchronize()
+            pair_frac = float(pairs.sum().item() / (len(fb) * (N * (N + 1) / 2.0)))
     out = {
         "metric": "sparse-prefill attention ms/layer at 128K + effective TFLOP/s vs dense",
         "value": dense_equiv_flops / (ms_step * 1e-3) / 1e12,
@@ -133,6 +146,7 @@ def bench_dict(args, sp, torch, np, CONFIGS, make_layer) -> int:
         "ms_per_layer": ms_step / nl,
         "computed_tflops": tiles * tile_flops / (ms_step * 1e-3) / 1e12 if tiles >= 0 else None,
         "fallback": args.fallback,
+        "vs_token_pair_fraction_last_layer": pair_frac,
         "vs_block_density_last_layer": (float(sum(vs_last[h].sum() for h in range(Hq) if role_h[-1][h] == -1)
                                               / max(1, int((role_h[-1] == -1).sum()) * dense_tiles_per_head))
                                         if vs else None),
@@ -163,8 +177,9 @@ def main() -> int:
     ap.add_argument("--dict-layers", type=int, default=0, metavar="L",
                     help="time L layers of one prompt through the cross-layer pattern dictionary "
                          "(sp_prefill_layer_dict; thresholds from --gate, default 10,0.2) and print that line instead")
-    ap.add_argument("--fallback", choices=["dense", "vs"], default="dense",
-                    help="with --dict-layers: what heads that fail Alg. 3 run (dense, or the vertical-slash pattern of Alg. 5)")
+    ap.add_argument("--fallback", choices=["dense", "vs", "vs-token"], default="dense",
+                    help="with --dict-layers: what heads that fail Alg. 3 run: dense, the vertical-slash pattern of "
+                         "Alg. 5 widened to whole key blocks (vs), or that pattern token by token (vs-token)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into a HIP graph and time replays (the calls enqueue kernels only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -170,7 +170,8 @@ __device__ __forceinline__ uint64_t bit_window(const uint64_t *bits, int nw, int
 // below the query block, the kept bands (mask = kept offsets, minus the kept keys already gathered) and the
 // diagonal block (causal; without forced blocks also restricted to kept keys / offsets).  Items are double
 // buffered in LDS (LDS-direct loads, one barrier per item); a wavefront whose 32 queries have no allowed key in an
-// item skips its matrix work.  Exact running max, the row sum adds the bf16-rounded weights PV sees.
+// item skips its matrix work.  Lazy softmax reference as in attn_kernel; the row sum adds the bf16-rounded weights
+// PV sees, every tile.
 template <int D, int B>
 __global__ __launch_bounds__(B * 2, 2) void vs_token_attn_kernel(VsTokParams p) {
   constexpr int NW = B / 32, SPB = B / KT, IMG = KT * D * 2, STAGE = 2 * IMG, DS = D / 16, DB = D / 32;
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(B * 2, 2) void vs_token_attn_kernel(VsTokParams p) 
 #pragma unroll
       for (int r = (rb == 0 ? 2 : 0); r < 16; r += 2) mx = max3f(mx, s[rb][r], s[rb][r + 1]);
     mx = max_xor32(mx);
-    const float m_new = fmaxf(m, mx * p.c);
+    const float m_new = lazy_max(m, mx * p.c);  // the reference lags the max by at most SP_MAX_SLACK (see attn_kernel.h)
     const float mref = (m_new == -INFINITY) ? 0.f : m_new;  // no allowed key yet: every weight below is 0
     const float alpha = (m == -INFINITY) ? 0.f : fast_exp2(m - mref);
     m = m_new;
