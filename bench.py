@@ -43,7 +43,8 @@ def kernel_source_digest() -> str:
     import hashlib
     h = hashlib.sha256()
     src = os.path.join(ROOT, "paper_2505_19578_amd", "csrc")
-    for name in sorted(os.listdir(src)) + ["../../include/shareprefill.h"]:
+    # the files that define the two attention kernels, their K/V images and their launch
+    for name in ["attn_kernel.h", "pack_kernel.h", "sp_common.h", "shareprefill.hip", "../../include/shareprefill.h"]:
         with open(os.path.join(src, name), "rb") as f:
             h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()[:16]
@@ -184,6 +185,9 @@ def main() -> int:
                     help="capture the step into a HIP graph and time replays (the calls enqueue kernels only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-all", action="store_true")
+    ap.add_argument("--sparse-one-per-cluster", action="store_true",
+                    help="after the timed steps, also launch the block-sparse kernel twice on one sharing head per "
+                         "cluster (for counter runs: how much of the K/V traffic the heads of a cluster share)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for HBM counters)")
     args = ap.parse_args()
@@ -314,6 +318,14 @@ def main() -> int:
     sparse_per_step = max(sparse_n // max(args.steps, 1), 1)     # sparse launches per step (2 with the gate)
     sparse_tflops = (sparse_tiles * tile_flops / sparse_per_step / (sparse_avg_ms * 1e-3) / 1e12
                      if sparse_avg_ms > 0 else 0.0)
+
+    if args.sparse_one_per_cluster:
+        sub = []
+        for c in range(C):
+            sub.append(next(h for h in range(Hq) if h2c[h] == c and h not in piv))
+        for _ in range(2):
+            sp.sp_block_sparse_attn(shape, q, k, v, sub, [h2c[h] for h in sub], kb_idx, kb_cnt, C, o, ws)
+        torch.cuda.synchronize()
 
     # the "vs dense" denominator: this library's own dense kernel on every head, no scores
     dense_all_ms = None
