@@ -489,7 +489,7 @@ sp_status launch_vertical_slash(const sp_shape *s, const void *q, const void *k,
 
 // workspace of the token-level vertical-slash attention for n listed heads per batch entry, after the search's own
 struct VsTokLayout {
-  size_t search, bits, cumv, gpos, cumband, bandlist, gimg, total;
+  size_t search, bits, cumv, gpos, cumband, bandlist, act, gimg, total;
 };
 VsTokLayout vs_token_layout(const sp_shape *s, int n) {
   const size_t maps = (size_t)s->batch * n, nqb = s->seq / s->block;
@@ -500,7 +500,8 @@ VsTokLayout vs_token_layout(const sp_shape *s, int n) {
   L.gpos = L.cumv + align_up(maps * (nqb + 1) * sizeof(int32_t), 256);
   L.cumband = L.gpos + align_up(maps * s->seq * sizeof(int32_t), 256);
   L.bandlist = L.cumband + align_up(maps * nqb * sizeof(int32_t), 256);
-  L.gimg = L.bandlist + align_up(maps * nqb * sizeof(int32_t), 256);
+  L.act = L.bandlist + align_up(maps * nqb * sizeof(int32_t), 256);
+  L.gimg = L.act + align_up((maps + s->batch) * sizeof(int32_t), 256);
   L.total = L.gimg + align_up(maps * (size_t)s->seq * s->head_dim * 2 * 2, 256);
   return L;
 }
@@ -541,12 +542,15 @@ sp_status launch_vs_token_attn(const sp_shape *s, const void *q, const void *k, 
   tp.cumband = (int32_t *)(ws + L.cumband);
   tp.bandlist = (int32_t *)(ws + L.bandlist);
   tp.gimg = ws + L.gimg;
+  tp.act_pos = (int32_t *)(ws + L.act);
+  tp.act_n = tp.act_pos + (size_t)s->batch * n;
+  tp.nch8 = ((tp.nqb + VST_TASK_ROWS - 1) / VST_TASK_ROWS + 7) / 8;
   tp.pairs = pairs;
   tp.role = role;
   for (int a = 0; a < n; ++a) tp.head_ids[a] = heads[a];
   ProfScope prof(KK_VS, st);
   hipLaunchKernelGGL(vs_token_prep_kernel, dim3(n, s->batch), dim3(1024), 0, st, tp);
-  const dim3 ggather(s->seq / KT, n, s->batch), gattn(tp.nqb, n, s->batch);
+  const dim3 ggather(s->seq / KT, n, s->batch), gattn((unsigned)((int64_t)s->batch * 8 * n * tp.nch8 * VST_TASK_ROWS));
   if (s->head_dim == 128)
     hipLaunchKernelGGL(vs_gather_kernel<128>, ggather, dim3(256), 0, st, tp);
   else
