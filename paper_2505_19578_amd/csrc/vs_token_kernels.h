@@ -258,8 +258,15 @@ __global__ __launch_bounds__(B * 2, 2) void vs_token_attn_kernel(VsTokParams p) 
   const int jmin = p.forced ? 1 : 0;
   const int n0 = (p.forced && i > 0) ? SPB : 0;
   const int G = p.cumv[hb * (p.nqb + 1) + i];
-  const int ng = (G + KT - 1) / KT;
-  const int nb = (i - jmin >= 1) ? p.cumband[hb * p.nqb + (i - jmin)] : 0;
+  // A row whose gathered items and kept bands together outnumber the key blocks below it walks all of those
+  // blocks instead, each with the mask kept offsets | kept keys (a head that keeps nearly everything would
+  // otherwise visit its kept keys twice: in the gathered images and, masked out, in the bands).
+  const int ng_list = (G + KT - 1) / KT;
+  const int nb_list = (i - jmin >= 1) ? p.cumband[hb * p.nqb + (i - jmin)] : 0;
+  const int nbelow = (i - jmin > 0) ? i - jmin : 0;  // key blocks strictly between the forced sink block and the diagonal
+  const bool walk_all = ng_list + nb_list * SPB > nbelow * SPB;
+  const int ng = walk_all ? 0 : ng_list;
+  const int nb = walk_all ? nbelow : nb_list;
   const int T = n0 + ng + nb * SPB + SPB;
   const char *kvbase = p.kvp + ((int64_t)b * p.n_kv_heads + kvh) * (int64_t)(p.seq / KT) * STAGE;
   const char *gbase = p.gimg + hb * (int64_t)(p.seq / KT) * STAGE;
@@ -271,7 +278,7 @@ __global__ __launch_bounds__(B * 2, 2) void vs_token_attn_kernel(VsTokParams p) 
     if (t < ng) return VsItem{gbase + (int64_t)t * STAGE, 1, 0, t};
     t -= ng;
     if (t < nb * SPB) {
-      const int j = i - bandlist[t / SPB], sub = t % SPB;
+      const int j = i - (walk_all ? 1 + t / SPB : bandlist[t / SPB]), sub = t % SPB;
       return VsItem{kvbase + (int64_t)(j * SPB + sub) * STAGE, 2, j, sub};
     }
     t -= nb * SPB;
@@ -308,7 +315,7 @@ __global__ __launch_bounds__(B * 2, 2) void vs_token_attn_kernel(VsTokParams p) 
     const uint64_t lo = rel ? pre.w1 : pre.w0, hi = rel ? pre.w2 : pre.w1;
     const uint64_t win = (lo >> sh) | ((hi << 1) << (63 - sh));
     const uint64_t R = __builtin_bitreverse64(win);
-    uint64_t M = pre.restricted ? (pre.kind == 2 ? (R & ~pre.v) : (R | pre.v)) : ~0ull;
+    uint64_t M = pre.restricted ? ((pre.kind == 2 && !walk_all) ? (R & ~pre.v) : (R | pre.v)) : ~0ull;
     if (pre.kind == 1) M = pre.nvalid >= KT ? ~0ull : (pre.nvalid <= 0 ? 0ull : ((1ull << pre.nvalid) - 1));
     if (pre.kind == 3) {  // causal: key 64 sub + kk <= tq
       const int top = pre.top0 + c32;
@@ -551,7 +558,7 @@ __global__ __launch_bounds__(B * 2, 2) void vs_token_attn_kernel(VsTokParams p) 
   int npairs = 0;  // at most 64 per item
   {
     f32x16 s_a[2], s_b[2];
-    const int U = n0 + G / KT;                      // items 0 .. U-1 have all-ones masks
+    const int U = n0 + (walk_all ? 0 : G / KT);     // items 0 .. U-1 have all-ones masks
     const int nfu = (U > 1) ? ((U - 1) & ~1) : 0;   // steps t < nfu: item t+1 is unmasked
     const int nfm = (T - 1 - nfu) & ~1;             // steps nfu <= t < nfu + nfm: the masked step (item t+1 exists)
     const VsItem it0 = item(0), it1 = item(1);

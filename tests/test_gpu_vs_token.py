@@ -42,9 +42,14 @@ def _pair_count(keep_v, keep_s, B, forced):
     return total
 
 
-@pytest.mark.parametrize("d,B,N,forced", [(128, 128, 1024, True), (128, 128, 1024, False), (128, 64, 576, True),
-                                          (64, 128, 768, True), (64, 64, 448, False)])
-def test_token_attention_random_inputs(d, B, N, forced):
+@pytest.mark.parametrize("d,B,N,forced,gamma", [(128, 128, 1024, True, 0.5), (128, 128, 1024, False, 0.5),
+                                                (128, 64, 576, True, 0.5), (64, 128, 768, True, 0.5),
+                                                (64, 64, 448, False, 0.5),
+                                                # nearly everything kept (long runs of full gathered items, every
+                                                # band), and nearly nothing
+                                                (128, 128, 1536, True, 0.98), (64, 64, 640, False, 0.98),
+                                                (128, 128, 1024, False, 0.02), (128, 64, 576, True, 0.02)])
+def test_token_attention_random_inputs(d, B, N, forced, gamma):
     import torch
     import oracle
     import paper_2505_19578_amd as sp
@@ -54,8 +59,8 @@ def test_token_attention_random_inputs(d, B, N, forced):
     _, _, vb = random_qkv(72, N, 4, 2, d, 1.0)     # |V| < 8: output rounding alone stays under the absolute bar
     q, k, v = to_dev(qb), to_dev(kb), to_dev(vb)
     hq, hk, hv = (bf16_bits_to_f32(x) for x in (qb, kb, vb))
-    heads, gamma = [0, 3, 2], 0.5
-    print(f"[vs token] d{d} B{B} N{N} forced {forced}", flush=True)
+    heads = [0, 3, 2]
+    print(f"[vs token] d{d} B{B} N{N} forced {forced} gamma {gamma}", flush=True)
     shape, o, bits, pairs = _run(sp, q, k, v, B, heads, gamma, forced)
     # the search's own sums on the same inputs (bit-identical run to run): what the kept sets must follow from
     ws = torch.empty(sp.sp_vs_workspace_bytes(shape, len(heads)), dtype=torch.uint8, device="cuda")
