@@ -52,9 +52,10 @@ def test_fused_layer_call_in_a_graph():
         assert np.isfinite(junk)
 
 
-def test_three_dictionary_layers_in_one_graph():
-    """Pivot election, sharing and the vertical-slash fallback are decided on the device: three layers of one
-    prompt, dictionary reset included, replay as one graph."""
+@pytest.mark.parametrize("token_level", [False, True])
+def test_three_dictionary_layers_in_one_graph(token_level):
+    """Pivot election, sharing and the vertical-slash fallback (block superset or token level) are decided on the
+    device: three layers of one prompt, dictionary reset included, replay as one graph."""
     import torch
     import paper_2505_19578_amd as sp
     Ls, dev = _layers(3, 1024)
@@ -63,7 +64,10 @@ def test_three_dictionary_layers_in_one_graph():
     nqb = cfg.seq // B
     h2c = [int(x) for x in Ls[0]["head_to_cluster"]]
     shape = sp.shape_of(dev[0]["q"], dev[0]["k"], None, B)
-    ws = torch.empty(sp.sp_workspace_bytes(shape, C) + sp.sp_vs_workspace_bytes(shape, Hq), dtype=torch.uint8, device="cuda")
+    vs_bytes = sp.sp_vs_token_workspace_bytes(shape, Hq) if token_level else sp.sp_vs_workspace_bytes(shape, Hq)
+    ws = torch.empty(sp.sp_workspace_bytes(shape, C) + vs_bytes, dtype=torch.uint8, device="cuda")
+    mode = dict(fallback_mode=sp.SP_FALLBACK_VERTICAL_SLASH_TOKEN) if token_level else \
+        dict(fallback_mode=sp.SP_FALLBACK_VERTICAL_SLASH, vs_idx=None, vs_cnt=None)
     valid = torch.zeros((1, C), dtype=torch.int32, device="cuda")
     a_t = torch.zeros((1, C, nqb), dtype=torch.float32, device="cuda")
     didx = torch.zeros((1, C, nqb, nqb), dtype=torch.int32, device="cuda")
@@ -77,13 +81,14 @@ def test_three_dictionary_layers_in_one_graph():
     outs = [torch.zeros_like(d["q"]) for d in dev]
     roles = [torch.zeros((1, Hq), dtype=torch.int32, device="cuda") for _ in dev]
     delta = 0.05        # between the heads' sparsity distances at this length: some fall back, some elect / share
+    if not token_level:
+        mode.update(vs_idx=vidx, vs_cnt=vcnt)
 
     def prefill():
         valid.zero_()
         for l, d in enumerate(dev):
             sp.sp_prefill_layer_dict(shape, d["q"], d["k"], d["v"], h2c, cfg.gamma, delta, 10.0, 0, 0, pd, outs[l],
-                                     scores, roles[l], a_hat, dist, ws,
-                                     fallback_mode=sp.SP_FALLBACK_VERTICAL_SLASH, vs_idx=vidx, vs_cnt=vcnt)
+                                     scores, roles[l], a_hat, dist, ws, **mode)
 
     prefill()
     torch.cuda.synchronize()
