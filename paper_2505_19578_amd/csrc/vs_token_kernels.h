@@ -201,8 +201,9 @@ struct VsMaskPre {
 // Same software pipeline as attn_kernel: K and V images ride in LDS rings filled two items ahead, one barrier per
 // item; while the matrix pipe runs S[t+1] = K[t+1] Q^T and O += V[t]^T P[t]^T the VALU computes P[t], then masks
 // S[t+1] and takes its row max (hand-laid groups).  The masks are built one item ahead from wave-uniform words of
-// the bitmaps (scalar loads).  A wavefront whose 32 queries have no allowed key in an item skips its matrix work
-// (general step).  Lazy softmax reference and the second normaliser sum as in attn_kernel.
+// the bitmaps (scalar loads).  In the pipelined steps a wavefront computes every item (an item without an allowed key
+// for its 32 queries contributes zeros); the general step of the last items skips such items.  Lazy softmax reference
+// and the second normaliser sum as in attn_kernel.
 template <int D, int B>
 __global__ __launch_bounds__(B * 2, 2) void vs_token_attn_kernel(VsTokParams p) {
   constexpr int NW = B / 32, SPB = B / KT, IMG = KT * D * 2, STAGE = 2 * IMG, DS = D / 16, DB = D / 32;
