@@ -183,7 +183,8 @@ def test_dict_batch_of_two_prompts_equals_two_single_runs():
     prompts = [[make_layer(cfg, layer=l, structure_layer=s0) for l in (s0, s0 + 1)] for s0 in (0, 20)]
     nqb = prompts[0][0]["cfg"].seq // B
     h2c = [int(x) for x in prompts[0][0]["head_to_cluster"]]
-    for fallback, delta in ((sp.SP_FALLBACK_DENSE, 10.0), (sp.SP_FALLBACK_VERTICAL_SLASH, 0.05)):
+    for fallback, delta in ((sp.SP_FALLBACK_DENSE, 10.0), (sp.SP_FALLBACK_VERTICAL_SLASH, 0.05),
+                            (sp.SP_FALLBACK_VERTICAL_SLASH_TOKEN, 0.05)):
         def run(batch_prompts):
             nb = len(batch_prompts)
             D = _Dict(sp, nb, C, nqb)
@@ -193,7 +194,8 @@ def test_dict_batch_of_two_prompts_equals_two_single_runs():
             for l in range(2):
                 q, k, v = (torch.cat([to_dev(p[l][x]) for p in batch_prompts], dim=0) for x in "qkv")
                 shape = sp.shape_of(q, k, None, B)
-                ws = torch.empty(sp.sp_workspace_bytes(shape, C) + sp.sp_vs_workspace_bytes(shape, Hq),
+                ws = torch.empty(sp.sp_workspace_bytes(shape, C) + max(sp.sp_vs_workspace_bytes(shape, Hq),
+                                                                         sp.sp_vs_token_workspace_bytes(shape, Hq)),
                                  dtype=torch.uint8, device="cuda")
                 o = torch.zeros_like(q)
                 scores = torch.zeros((nb, C, nqb, nqb), dtype=torch.float32, device="cuda")
@@ -201,8 +203,9 @@ def test_dict_batch_of_two_prompts_equals_two_single_runs():
                 a_hat = torch.empty((nb, Hq, nqb), dtype=torch.float32, device="cuda")
                 dist = torch.empty((nb, Hq, 2), dtype=torch.float32, device="cuda")
                 print(f"[dict batch {nb}] layer {l} fallback {fallback}", flush=True)
+                lists = {} if fallback == sp.SP_FALLBACK_VERTICAL_SLASH_TOKEN else dict(vs_idx=vs_idx, vs_cnt=vs_cnt)
                 sp.sp_prefill_layer_dict(shape, q, k, v, h2c, cfg.gamma, delta, 10.0, 0, 0, D.c, o, scores, role, a_hat,
-                                         dist, ws, fallback_mode=fallback, vs_idx=vs_idx, vs_cnt=vs_cnt)
+                                         dist, ws, fallback_mode=fallback, **lists)
                 torch.cuda.synchronize()
                 outs.append((o.clone(), role.clone(), dist.clone(), a_hat.clone()))
             return outs, D
@@ -219,7 +222,7 @@ def test_dict_batch_of_two_prompts_equals_two_single_runs():
                     assert torch.equal(Db.a_tilde[n, c], Ds.a_tilde[0, c])
         roles = both[0][1].cpu().numpy()
         print(f"[dict batch 2] fallback {fallback}: layer-0 roles {roles.tolist()}", flush=True)
-        if fallback == sp.SP_FALLBACK_VERTICAL_SLASH:
+        if fallback != sp.SP_FALLBACK_DENSE:
             assert (roles == -1).any()
 
 
