@@ -187,6 +187,21 @@ def test_calls_reject_bad_arguments_without_launching():
     assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
     # slab of raw logits (block x seq fp32 per head) dominates the search's workspace
     assert sp.sp_vs_workspace_bytes(s, 2) >= 2 * 64 * 1024 * 4 + 2 * 2 * 1024 * 4
+    # attention over the token-level pattern of Alg. 5
+    tok = lambda gamma, bits, ws_bytes, o=fake: L.sp_vertical_slash_attn(
+        ctypes.byref(s), fake, fake, fake, ids, 2, ctypes.c_float(gamma), 1, o, bits, None, fake, ws_bytes, None)
+    rc = tok(1.5, None, 1 << 40)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"gamma" in L.sp_last_error()
+    rc = tok(0.9, 4100, 1 << 40)                       # a bitmap pointer that is not 8-byte aligned
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG" and b"keep_bits" in L.sp_last_error()
+    rc = tok(0.9, None, 1 << 40, o=None)
+    assert L.sp_status_string(rc) == b"SP_ERR_INVALID_ARG"
+    rc = tok(0.9, None, 4096)
+    assert L.sp_status_string(rc) == b"SP_ERR_WORKSPACE"
+    # on top of the search's workspace: bitmaps, ranks of the kept keys (seq ints) and one more packed K/V copy per head
+    extra = sp.sp_vs_token_workspace_bytes(s, 2) - sp.sp_vs_workspace_bytes(s, 2)
+    assert extra >= 2 * (2 * (s.seq // 8) + s.seq * 4 + s.seq * s.head_dim * 2 * 2)
+    assert sp.sp_vs_token_workspace_bytes(s, 4) > sp.sp_vs_token_workspace_bytes(s, 2)
 
 
 def test_generator_is_deterministic_and_bf16_round_trip():
