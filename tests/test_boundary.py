@@ -240,14 +240,3 @@ def test_bench_refuses_more_than_one_gpu():
                          text=True, timeout=120)
     assert res.returncode != 0
     assert "single-GPU" in res.stderr and res.stdout.strip() == ""
-
-
-def test_bench_refuses_more_than_one_gpu():
-    """The build is single-GPU: bench.py --gpus N with N > 1 exits with a message and launches nothing."""
-    import os
-    import subprocess
-    import sys
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
-    assert res.returncode != 0
-    assert "single-GPU" in (res.stdout + res.stderr)
